@@ -1,0 +1,79 @@
+/*
+ * fa.h -- C ABI of the MI355X (gfx950) exact attention forward library.
+ *
+ * The operation is the attention of FastAttention section 5.1 / appendix C
+ * (prefill and decoding equations), O = softmax(scale * Q K^T + mask) V, with the
+ * lower-triangular mask of section 4.1 generated from indices per tile (no mask
+ * tensor exists), evaluated tile by tile with the online-softmax dataflow of
+ * appendix A (Q K^T, exp, exp * V, running row max / row sum).
+ *
+ * All entry points are plain C: device pointers and sizes, no C++ or torch types.
+ */
+#ifndef FA_H
+#define FA_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes (0 = success); every argument error is detected on the host before any HIP call */
+#define FA_OK            0
+#define FA_ERR_NULL     -1 /* a required pointer is NULL */
+#define FA_ERR_SHAPE    -2 /* B, H, Nq or Nk <= 0, or a tensor/grid too large to index */
+#define FA_ERR_HEADDIM  -3 /* D is not 64 or 128 */
+#define FA_ERR_DTYPE    -4 /* dtype is not FA_DTYPE_F16 or FA_DTYPE_BF16 */
+#define FA_ERR_SCALE    -5 /* scale is NaN or infinite */
+#define FA_ERR_ALIGN    -6 /* q, k, v or o not 16-byte aligned, or lse not 4-byte aligned */
+#define FA_ERR_LAUNCH   -7 /* the HIP runtime rejected the launch (see fa_last_hip_error) */
+
+#define FA_DTYPE_F16  0 /* IEEE binary16 */
+#define FA_DTYPE_BF16 1 /* bfloat16 */
+
+/*
+ * fa_fwd -- exact attention forward (appendix A dataflow; section 4.1 mask handling:
+ * tiles entirely above the diagonal are skipped, tiles entirely below it take no
+ * mask, only tiles that straddle it get a per-element predicate).
+ *
+ * For every batch b, head h and query row i:
+ *     J_i    = all keys                    (causal == 0)
+ *            = { j : j <= i + (Nk - Nq) }  (causal != 0; bottom-right aligned, so a
+ *              single decode query attends to the whole cache, appendix C)
+ *     s_ij   = scale * sum_d q[b,h,i,d] * k[b,h,j,d]
+ *     o[b,h,i,:] = sum_{j in J_i} softmax_j(s_ij) * v[b,h,j,:]    rounded to dtype
+ *     lse[b,h,i] = ln sum_{j in J_i} exp(s_ij)                     (natural log, fp32)
+ *     rows with empty J_i (causal, Nq > Nk): o = 0, lse = -inf.
+ *
+ * Arguments
+ *   q, o   : DEVICE pointers, [B, H, Nq, D] contiguous, D fastest, 16-bit elements of `dtype`
+ *   k, v   : DEVICE pointers, [B, H, Nk, D] contiguous
+ *   lse    : DEVICE pointer,  [B, H, Nq] fp32
+ *   D      : 64 or 128
+ *   scale  : any finite float (1/sqrt(D) in the paper)
+ *   dtype  : FA_DTYPE_F16 or FA_DTYPE_BF16; both products accumulate in fp32 on MFMA,
+ *            the probabilities are rounded to `dtype` before the second product
+ *   stream : hipStream_t (as void*); NULL is the default stream
+ *
+ * Ownership: the caller owns every buffer; the library allocates nothing, keeps no
+ * state between calls, needs no workspace and enqueues exactly one kernel on `stream`
+ * without synchronising.  o and lse must not alias the inputs.  q, k, v, o must be
+ * 16-byte aligned.  Nq and Nk need not be multiples of any tile size.
+ *
+ * Returns FA_OK or a negative FA_ERR_* code; on an argument error nothing is launched.
+ */
+int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+           int B, int H, int Nq, int Nk, int D, float scale, int causal, int dtype,
+           void *stream);
+
+/* static, never-freed description of an FA_ERR_* code */
+const char *fa_strerror(int code);
+
+/* library version, major * 10000 + minor * 100 + patch */
+int fa_version(void);
+
+/* hipError_t value of the last launch failure seen by this thread (0 if none) */
+int fa_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA_H */

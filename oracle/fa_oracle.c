@@ -1,0 +1,185 @@
+/*
+ * CPU oracle for exact attention forward -- TEST INFRASTRUCTURE, not a product path.
+ *
+ * Computes, for every (batch b, head h, query row i), the plain definition of
+ * attention that the tiled method must reproduce (FastAttention section 5.1,
+ * "standard attention": Softmax(Q K^T / sqrt(d)) V with no fusion and no online
+ * softmax; appendix C, prefill equation for X_O; section 4.1: the mask is lower
+ * triangular).  Everything is fp64; inputs are fp16/bf16 bit patterns widened
+ * exactly.  No blocking, no running maximum, no reordering: one row of logits is
+ * materialised, then its maximum, then the weights, then the weighted sum.
+ *
+ *   J_i   = all keys (non-causal), or { j : j <= i + (Nk - Nq) } (causal,
+ *           bottom-right aligned so that a single decode query sees the whole
+ *           cache as in appendix C's decoding equations)
+ *   s_ij  = scale * sum_d q[i,d] k[j,d]                       j in J_i
+ *   m_i   = max_j s_ij ;  w_ij = exp(s_ij - m_i) ;  l_i = sum_j w_ij
+ *   o_i   = (sum_j w_ij v_j) / l_i ;  lse_i = m_i + ln(l_i)
+ *   rows with empty J_i:  o_i = 0, lse_i = -inf
+ *
+ * Layout: q [B,H,Nq,D], k,v [B,H,Nk,D], contiguous, D fastest, host pointers,
+ * uint16 bit patterns (dtype 0 = IEEE fp16, 1 = bfloat16).
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call this.
+ * It shares no code with the GPU library.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double half_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double x;
+    if (e == 0) {
+        x = ldexp((double)f, -24);             /* zero and subnormals: f * 2^-24 */
+    } else if (e == 31) {
+        x = f ? NAN : INFINITY;
+    } else {
+        x = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    }
+    return sign ? -x : x;
+}
+
+static double bf16_to_double(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;            /* bfloat16 is the top half of a binary32 */
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double widen(uint16_t bits, int dtype) {
+    return dtype == 0 ? half_to_double(bits) : bf16_to_double(bits);
+}
+
+/* number of keys row i may attend to (keys 0 .. count-1) */
+static int64_t visible_count(int64_t i, int Nq, int Nk, int causal) {
+    if (!causal) return Nk;
+    int64_t c = i + ((int64_t)Nk - (int64_t)Nq) + 1;
+    if (c < 0) c = 0;
+    if (c > Nk) c = Nk;
+    return c;
+}
+
+/*
+ * Steps 1-3 for one row: logits s[0..n), their maximum, the unnormalised
+ * weights w[j] = exp(s[j] - m) written over s, and l = sum w.  Returns n.
+ */
+static int64_t row_weights(const uint16_t *q_row, const uint16_t *k_head, int64_t n, int D,
+                           double scale, int dtype, double *s, double *m_out, double *l_out) {
+    double m = -INFINITY;
+    for (int64_t j = 0; j < n; ++j) {
+        const uint16_t *k_row = k_head + j * D;
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d) dot += widen(q_row[d], dtype) * widen(k_row[d], dtype);
+        s[j] = scale * dot;
+        if (s[j] > m) m = s[j];
+    }
+    double l = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        s[j] = exp(s[j] - m);
+        l += s[j];
+    }
+    *m_out = m;
+    *l_out = l;
+    return n;
+}
+
+static int bad_args(const void *q, const void *k, const void *v, int B, int H, int Nq, int Nk, int D,
+                    int dtype) {
+    if (!q || !k || !v) return -1;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || D <= 0) return -2;
+    if (dtype != 0 && dtype != 1) return -4;
+    return 0;
+}
+
+/*
+ * Full forward.  rows == NULL: every row, o is [B,H,Nq,D], lse is [B,H,Nq].
+ * rows != NULL: only the nrows flat row ids (b*H + h)*Nq + i listed; o is
+ * [nrows,D], lse is [nrows], in the order listed.
+ * nthreads <= 0: OpenMP default.  Returns 0, or <0 on bad arguments.
+ */
+int fa_oracle_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
+                  int B, int H, int Nq, int Nk, int D, double scale, int causal, int dtype,
+                  const int64_t *rows, int64_t nrows, int nthreads) {
+    int err = bad_args(q, k, v, B, H, Nq, Nk, D, dtype);
+    if (err) return err;
+    if (!o || !lse) return -1;
+    int64_t total = rows ? nrows : (int64_t)B * H * Nq;
+    if (rows) {
+        for (int64_t r = 0; r < nrows; ++r)
+            if (rows[r] < 0 || rows[r] >= (int64_t)B * H * Nq) return -2;
+    }
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)Nk);
+        if (!s) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t r = 0; r < total; ++r) {
+            if (!s) continue;
+            int64_t flat = rows ? rows[r] : r;
+            int64_t i = flat % Nq;
+            int64_t bh = flat / Nq;
+            const uint16_t *q_row = q + flat * D;
+            const uint16_t *k_head = k + bh * (int64_t)Nk * D;
+            const uint16_t *v_head = v + bh * (int64_t)Nk * D;
+            double *o_row = o + r * D;
+            int64_t n = visible_count(i, Nq, Nk, causal);
+            if (n == 0) {
+                for (int d = 0; d < D; ++d) o_row[d] = 0.0;
+                lse[r] = -INFINITY;
+                continue;
+            }
+            double m, l;
+            row_weights(q_row, k_head, n, D, scale, dtype, s, &m, &l);
+            for (int d = 0; d < D; ++d) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < n; ++j) acc += s[j] * widen(v_head[j * D + d], dtype);
+                o_row[d] = acc / l;
+            }
+            lse[r] = m + log(l);
+        }
+        free(s);
+    }
+    return failed ? -8 : 0;
+}
+
+/*
+ * Normalised attention probabilities of ONE row (flat id as above):
+ * p[j] = w_ij / l_i for j in J_i and 0 for masked keys; p has Nk entries.
+ * Exposed so that tests can pin the softmax step on its own.
+ */
+int fa_oracle_probs(const uint16_t *q, const uint16_t *k, double *p, int B, int H, int Nq, int Nk,
+                    int D, double scale, int causal, int dtype, int64_t row) {
+    int err = bad_args(q, k, k, B, H, Nq, Nk, D, dtype);
+    if (err) return err;
+    if (!p) return -1;
+    if (row < 0 || row >= (int64_t)B * H * Nq) return -2;
+    int64_t i = row % Nq, bh = row / Nq;
+    int64_t n = visible_count(i, Nq, Nk, causal);
+    for (int64_t j = 0; j < Nk; ++j) p[j] = 0.0;
+    if (n == 0) return 0;
+    double m, l;
+    row_weights(q + row * D, k + bh * (int64_t)Nk * D, n, D, scale, dtype, p, &m, &l);
+    for (int64_t j = 0; j < n; ++j) p[j] /= l;
+    return 0;
+}
+
+int fa_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
