@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention forward on one MI355X.
+
+A step is one fa_fwd launch over one batch of synthetic input already resident in HBM.
+Prints ONE JSON line: whole-job TFLOP/s on the headline workload (benchmark configs[1]),
+the roofline figures of the kernel measured with HIP events on the launch stream, the CPU
+oracle timed on the host cores, and (unless --no-extra) the other full-size configurations.
+
+FLOP convention (section 5.2.3 of the paper, times the batch): 4*B*H*Nq*Nk*D, halved when causal.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA peak
+METRIC = "attention fwd TFLOP/s and % of MFMA fp16/bf16 peak (1 MI355X)"
+
+
+def device_inputs_host_recipe(cfg, torch, np, I):
+    """The seeded numpy recipe (exactly the tensors the parity tests check), copied to the GPU."""
+    q, k, v = I.make_qkv(cfg)
+    dev = torch.device("cuda:0")
+    return tuple(torch.from_numpy(a.view(np.int16)).to(dev) for a in (q, k, v)), (q, k, v)
+
+
+def device_inputs_on_gpu(cfg, torch):
+    """Same distribution, drawn on the GPU from torch's seeded generator (for the large extras)."""
+    dev = torch.device("cuda:0")
+    tdt = torch.float16 if cfg.dtype == 0 else torch.bfloat16
+    g = torch.Generator(device=dev)
+    out = []
+    for seed, n in zip(cfg.seeds, (cfg.Nq, cfg.Nk, cfg.Nk)):
+        g.manual_seed(seed)
+        t = torch.empty((cfg.B, cfg.H, n, cfg.D), dtype=tdt, device=dev)
+        for b in range(cfg.B):   # per batch entry: bounds the fp32 temporary
+            x = torch.randn((cfg.H, n, cfg.D), generator=g, device=dev, dtype=torch.float32)
+            t[b] = (x * cfg.mult).to(tdt)
+        out.append(t.view(torch.int16))
+    return tuple(out)
+
+
+def time_config(cfg, tensors, steps, warmup, torch, fa):
+    """Warm up, then time exactly `steps` launches. Returns wall ms/step and the HIP-event mean ms/launch."""
+    tq, tk, tv = tensors
+    dev = tq.device
+    to = torch.empty((cfg.B, cfg.H, cfg.Nq, cfg.D), dtype=torch.int16, device=dev)
+    tl = torch.empty((cfg.B, cfg.H, cfg.Nq), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+
+    def launch():
+        fa.fa_fwd(tq, tk, tv, to, tl, cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, cfg.scale, int(cfg.causal), cfg.dtype, sp)
+
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)          # HIP events on the stream the kernel is launched on
+    for _ in range(steps):
+        launch()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / steps
+    event_ms = ev0.elapsed_time(ev1) / steps
+    return wall_ms, event_ms, (to, tl)
+
+
+def read_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"fa_fwd_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_16663_amd import binding as fa
+    from paper_2410_16663_amd import inputs as I
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    fa.load()   # fails loudly if libfa.so is missing; there is no fallback
+    torch.cuda.set_device(0)
+
+    cfg = I.CONFIGS[args.workload]
+    tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
+    wall_ms, event_ms, _ = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
+    flops = cfg.flops()
+    value = flops / (wall_ms * 1e-3) / 1e12
+    achieved = flops / (event_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if cfg.dtype == 0 else "bf16", "data": "synthetic",
+        "pct_of_mfma_peak": round(100.0 * value / MFMA_PEAK_TFLOPS, 2),
+        "config": {"workload": cfg.describe(), "flop_convention": "4*B*H*Nq*Nk*D, halved when causal",
+                   "accumulate": "fp32", "inputs": "N(0,1) numpy PCG64 seeds %s, resident in HBM" % (cfg.seeds,),
+                   "note": "Q,K,V,O of this workload (64 MiB) fit in the 256 MiB Infinity Cache"},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic(cfg.name),
+                     "kernel": "fa_fwd_kernel", "avg_launch_ms": round(event_ms, 5),
+                     "flops_per_launch": flops},
+    }
+
+    if not args.no_cpu:
+        import oracle
+        q, k, v = host
+        nthreads = min(oracle.num_threads(), os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": nthreads,
+                               "kind": "oracle", "seconds": round(dt, 3),
+                               "sample": f"all {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name}, one pass, fp64"}
+
+    if not args.no_extra:
+        extra = {}
+        for name in ("C3", "C4", "C5"):
+            if name == cfg.name:
+                continue
+            c = I.CONFIGS[name]
+            del tensors
+            torch.cuda.empty_cache()
+            tensors = device_inputs_on_gpu(c, torch)
+            steps = 3 if name == "C5" else 10
+            w_ms, e_ms, _ = time_config(c, tensors, steps, 2, torch, fa)
+            tf = c.flops() / (e_ms * 1e-3) / 1e12
+            extra[name] = {"workload": c.describe(), "ms_per_launch": round(e_ms, 4), "tflops": round(tf, 2),
+                           "pct_of_mfma_peak": round(100.0 * tf / MFMA_PEAK_TFLOPS, 2), "steps": steps,
+                           "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)"}
+        out["other_workloads"] = extra
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

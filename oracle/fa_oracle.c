@@ -52,9 +52,27 @@ static double bf16_to_double(uint16_t h) {
     return (double)f;
 }
 
-static double widen(uint16_t bits, int dtype) {
-    return dtype == 0 ? half_to_double(bits) : bf16_to_double(bits);
+/*
+ * Decoding is done once per bit pattern: table[dtype][bits] holds the exact value of
+ * every 16-bit pattern, filled from the two decoders above on first use.
+ */
+static double widen_table[2][65536];
+static int widen_ready = 0;
+
+static void widen_init(void) {
+#pragma omp critical(fa_oracle_widen)
+    {
+        if (!widen_ready) {
+            for (int b = 0; b < 65536; ++b) {
+                widen_table[0][b] = half_to_double((uint16_t)b);
+                widen_table[1][b] = bf16_to_double((uint16_t)b);
+            }
+            widen_ready = 1;
+        }
+    }
 }
+
+static double widen(uint16_t bits, int dtype) { return widen_table[dtype][bits]; }
 
 /* number of keys row i may attend to (keys 0 .. count-1) */
 static int64_t visible_count(int64_t i, int Nq, int Nk, int causal) {
@@ -110,6 +128,7 @@ int fa_oracle_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, doubl
     if (err) return err;
     if (!o || !lse) return -1;
     int64_t total = rows ? nrows : (int64_t)B * H * Nq;
+    widen_init();
     if (rows) {
         for (int64_t r = 0; r < nrows; ++r)
             if (rows[r] < 0 || rows[r] >= (int64_t)B * H * Nq) return -2;
@@ -143,11 +162,11 @@ int fa_oracle_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, doubl
             }
             double m, l;
             row_weights(q_row, k_head, n, D, scale, dtype, s, &m, &l);
-            for (int d = 0; d < D; ++d) {
-                double acc = 0.0;
-                for (int64_t j = 0; j < n; ++j) acc += s[j] * widen(v_head[j * D + d], dtype);
-                o_row[d] = acc / l;
-            }
+            /* o_row[d] = (sum over j, in increasing j, of w_ij v[j,d]) / l_i */
+            for (int d = 0; d < D; ++d) o_row[d] = 0.0;
+            for (int64_t j = 0; j < n; ++j)
+                for (int d = 0; d < D; ++d) o_row[d] += s[j] * widen(v_head[j * D + d], dtype);
+            for (int d = 0; d < D; ++d) o_row[d] /= l;
             lse[r] = m + log(l);
         }
         free(s);
@@ -170,6 +189,7 @@ int fa_oracle_probs(const uint16_t *q, const uint16_t *k, double *p, int B, int 
     int64_t n = visible_count(i, Nq, Nk, causal);
     for (int64_t j = 0; j < Nk; ++j) p[j] = 0.0;
     if (n == 0) return 0;
+    widen_init();
     double m, l;
     row_weights(q + row * D, k + bh * (int64_t)Nk * D, n, D, scale, dtype, p, &m, &l);
     for (int64_t j = 0; j < n; ++j) p[j] /= l;

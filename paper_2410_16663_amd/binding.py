@@ -1,0 +1,93 @@
+"""ctypes view of the C ABI declared in include/fa.h -- argument marshalling only.
+
+Every step of the attention forward runs inside libfa.so's HIP kernels.  There is no
+fallback: if the library is missing, loading raises.  torch is optional here; device
+buffers may be passed as raw integer addresses or as anything with ``data_ptr()``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfa.so")
+
+FA_OK = 0
+FA_ERR_NULL = -1
+FA_ERR_SHAPE = -2
+FA_ERR_HEADDIM = -3
+FA_ERR_DTYPE = -4
+FA_ERR_SCALE = -5
+FA_ERR_ALIGN = -6
+FA_ERR_LAUNCH = -7
+FA_DTYPE_F16 = 0
+FA_DTYPE_BF16 = 1
+
+# every symbol include/fa.h declares
+EXPORTS = ("fa_fwd", "fa_strerror", "fa_version", "fa_last_hip_error")
+
+_lib = None
+
+
+class FaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"fa error {code}: {fa_strerror(code)}")
+
+
+def load() -> ctypes.CDLL:
+    """Load libfa.so (built by paper_2410_16663_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_16663_amd.build` "
+                "(there is no non-HIP fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        lib.fa_fwd.restype = ctypes.c_int
+        lib.fa_fwd.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
+            ctypes.c_float, ctypes.c_int, ctypes.c_int, vp]
+        lib.fa_strerror.restype = ctypes.c_char_p
+        lib.fa_strerror.argtypes = [ctypes.c_int]
+        lib.fa_version.restype = ctypes.c_int
+        lib.fa_version.argtypes = []
+        lib.fa_last_hip_error.restype = ctypes.c_int
+        lib.fa_last_hip_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _addr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    raise TypeError("pass a device address (int) or an object with data_ptr()")
+
+
+def fa_fwd_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream=0) -> int:
+    """Call fa_fwd and return its status code unchanged."""
+    return load().fa_fwd(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nq), int(Nk),
+                         int(D), float(scale), int(causal), int(dtype), _addr(stream))
+
+
+def fa_fwd(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream=0) -> None:
+    """fa_fwd of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_fwd_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_strerror(code: int) -> str:
+    return load().fa_strerror(int(code)).decode()
+
+
+def fa_version() -> int:
+    return load().fa_version()
+
+
+def fa_last_hip_error() -> int:
+    return load().fa_last_hip_error()

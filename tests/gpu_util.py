@@ -1,0 +1,61 @@
+"""Helpers for the GPU parity tests: device buffers via torch, calls through the C ABI."""
+import numpy as np
+
+from paper_2410_16663_amd import binding as fa
+from paper_2410_16663_amd import inputs as I
+
+O_MAX_ABS = 1e-2     # tolerance on O, max over elements
+O_MEAN_ABS = 1e-3    # tolerance on O, mean over elements
+LSE_ABS = 1e-3       # tolerance on log-sum-exp
+
+
+def run_fa_fwd(q_bits, k_bits, v_bits, scale, causal, dtype, keep_device=False):
+    """Copy the uint16 inputs to the GPU, run fa_fwd through the C ABI, return (o_bits, lse) as numpy."""
+    import torch
+    assert torch.cuda.is_available()
+    B, H, Nq, D = q_bits.shape
+    Nk = k_bits.shape[2]
+    dev = torch.device("cuda:0")
+    tq = torch.from_numpy(q_bits.view(np.int16)).to(dev)
+    tk = torch.from_numpy(k_bits.view(np.int16)).to(dev)
+    tv = torch.from_numpy(v_bits.view(np.int16)).to(dev)
+    # poison the outputs so that anything left unwritten shows up
+    to = torch.full((B, H, Nq, D), 0x7E00 if dtype == I.F16 else 0x7FC0, dtype=torch.int16, device=dev)
+    tl = torch.full((B, H, Nq), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    fa.fa_fwd(tq, tk, tv, to, tl, B, H, Nq, Nk, D, scale, int(causal), dtype, stream)
+    torch.cuda.synchronize()
+    if keep_device:
+        return (tq, tk, tv, to, tl)
+    return to.cpu().numpy().view(np.uint16), tl.cpu().numpy()
+
+
+def bf16_half_ulp(x):
+    """Half a unit in the last place of bfloat16 (8 significant bits) at magnitude |x|."""
+    ax = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 8)
+
+
+def check_against_oracle(o_bits, lse, o_ref, lse_ref, dtype, label=""):
+    """Assert the stated tolerances. o_bits/o_ref and lse/lse_ref have matching shapes."""
+    o = I.bits_to_f64(o_bits, dtype).reshape(o_ref.shape)
+    assert np.isfinite(o).all(), f"{label}: non-finite or unwritten output"
+    err = np.abs(o - o_ref)
+    tol = np.full_like(err, O_MAX_ABS)
+    if dtype == I.BF16:
+        # a bf16 result cannot be closer to the oracle than its own rounding allows: where half an
+        # ulp of the output format is a large part of the budget, allow it on top of a 5e-3 budget
+        tol = np.maximum(tol, bf16_half_ulp(o_ref) + 5e-3)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert (err <= tol).all(), (f"{label}: O max-abs {err.max():.3e}; worst at {worst}: got {o[worst]!r} "
+                                f"want {o_ref[worst]!r} (tol {tol[worst]:.3e})")
+    assert err.mean() <= O_MEAN_ABS, f"{label}: O mean-abs {err.mean():.3e}"
+    lse = np.asarray(lse, dtype=np.float64).reshape(lse_ref.shape)
+    inf = np.isneginf(lse_ref)
+    assert np.array_equal(np.isneginf(lse), inf), f"{label}: -inf pattern of lse differs"
+    lerr = np.abs(lse[~inf] - lse_ref[~inf])
+    assert not np.isnan(lse[~inf]).any(), f"{label}: NaN in lse"
+    if lerr.size:
+        assert lerr.max() <= LSE_ABS, f"{label}: lse max-abs {lerr.max():.3e}"
+    return dict(o_max=float(err.max()), o_mean=float(err.mean()), lse_max=float(lerr.max()) if lerr.size else 0.0,
+                n_over_1e2=int((err > O_MAX_ABS).sum()))
