@@ -94,6 +94,11 @@ def main():
     ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--gpu-inputs", action="store_true",
+                    help="draw the headline workload's inputs on the GPU (implies --no-cpu); for profiling runs")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also launch a plain device copy of this many MiB (a known-size reference "
+                         "for the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -109,7 +114,19 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = I.CONFIGS[args.workload]
-    tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.gpu_inputs:
+        args.no_cpu = True
+        tensors, host = device_inputs_on_gpu(cfg, torch), None
+    else:
+        tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
     wall_ms, event_ms, _ = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
     flops = cfg.flops()
     value = flops / (wall_ms * 1e-3) / 1e12
