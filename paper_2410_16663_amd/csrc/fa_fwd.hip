@@ -118,6 +118,17 @@ __device__ __forceinline__ float xhalf_sum(float x) {
     return lo + hi;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane i's data lands at
+// lds_addr + 16*i.  Issued as inline asm so that the compiler does not put a vmcnt(0) wait
+// in front of every later LDS read (it cannot tell the buffers apart); the kernel waits
+// for vmcnt(0) itself before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory", "m0");
+}
+
 template <int DT, int D, bool CAUSAL, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int NT = NW * 64;
@@ -176,69 +187,102 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
         }
     }
 
-    // ---- staging registers for the next K/V tile
-    s16x8 kreg[PER], vreg[PER];
-    auto load_tile = [&](int t) {
+    // ---- K/V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per
+    // lane, no staging registers).  One such instruction fills 1 KiB of LDS contiguously in
+    // lane order, so the bank swizzle is applied on the global side: the lane that owns LDS
+    // slot (row r, chunk c') fetches the global chunk that the swizzle maps there.
+    constexpr int NI = TILEB / 1024 / NW;         // load instructions per wave per tile
+    static_assert(TILEB % (1024 * NW) == 0, "tile must split evenly over the waves");
+    int k_src[NI], v_src[NI], ld_row[NI];         // per-lane source byte offsets inside a tile row block
 #pragma unroll
-        for (int n = 0; n < PER; ++n) {
-            const int id = tid + n * NT;
-            const int r = id / CPR, c = id % CPR;
-            const int key = t * BN + r;
-            if (key < Nk) {
-                kreg[n] = *(const s16x8 *)(kg + (size_t)key * D + c * 8);
-                vreg[n] = *(const s16x8 *)(vg + (size_t)key * D + c * 8);
-            } else {
-                kreg[n] = (s16x8)(0);
-                vreg[n] = (s16x8)(0);
-            }
+    for (int n = 0; n < NI; ++n) {
+        const int slot = (wave * NI + n) * 1024 + lane * 16;   // LDS byte this lane fills
+        const int r = slot / ROWB, cs = (slot % ROWB) >> 4;
+        int ck, cv;
+        if constexpr (D == 128) {
+            ck = cs ^ (r & 15);
+            cv = cs ^ ((r & 3) << 2);
+        } else {
+            ck = cs ^ ((r >> 1) & 7);
+            cv = cs ^ (((r >> 1) & 1) << 2);
+        }
+        ld_row[n] = r;
+        k_src[n] = ck * 16;
+        v_src[n] = cv * 16;
+    }
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, smem));
+    const unsigned char *kgb = (const unsigned char *)kg;
+    const unsigned char *vgb = (const unsigned char *)vg;
+    auto load_k = [&](int t, int buf) {
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            const int key = min(t * BN + ld_row[n], Nk - 1);   // rows past the end re-read the last key; they are masked
+            dma16_to_lds(kgb, (unsigned)(key * ROWB + k_src[n]), lds_base + buf * TILEB + (wave * NI + n) * 1024);
         }
     };
-    auto store_tile = [&](int buf) {
+    auto load_v = [&](int t, int buf) {
 #pragma unroll
-        for (int n = 0; n < PER; ++n) {
-            const int id = tid + n * NT;
-            const int r = id / CPR, c = id % CPR;
-            *(s16x8 *)(smem + buf * TILEB + k_lds_off<D>(r, c)) = kreg[n];
-            *(s16x8 *)(smem + (2 + buf) * TILEB + v_lds_off<D>(r, c * 16)) = vreg[n];
+        for (int n = 0; n < NI; ++n) {
+            const int key = min(t * BN + ld_row[n], Nk - 1);
+            dma16_to_lds(vgb, (unsigned)(key * ROWB + v_src[n]), lds_base + (2 + buf) * TILEB + (wave * NI + n) * 1024);
+        }
+    };
+
+    // S^T = K Q^T for one 64-key tile held in K buffer `buf`
+    auto qk_tile = [&](int buf, f32x16 (&s)[2]) {
+        const unsigned char *ks = smem + buf * TILEB;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            s[mb] = (f32x16)(0.f);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const s16x8 a = *(const s16x8 *)(ks + k_lds_off<D>(mb * 32 + l32, 2 * kb + h));
+                s[mb] = mfma32<DT>(a, qf[kb], s[mb]);
+            }
         }
     };
 
     f32x16 oacc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) oacc[db] = (f32x16)(0.f);
-    float m_run = -INFINITY;   // running max of the unscaled logits of this lane's query
-    float l_run = 0.f;         // this half-wave's share of the running row sum
-
-    if (nt > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
-    __syncthreads();
+    // Softmax state, in log2 units (logit * c).  m_ref is the reference actually subtracted
+    // before exponentiation; it follows the running maximum lazily (only when the maximum
+    // has moved by more than RESCALE_TAU), which keeps exp2 arguments <= RESCALE_TAU and
+    // spares the rescale of the accumulator on most tiles.  Any reference gives the same
+    // quotient O = acc / l.
+    constexpr float RESCALE_TAU = 8.f;
+    float m_ref = -1e30f;
+    float l_run = 0.f;         // this half-wave's share of the row sum, relative to m_ref
 
     // per-lane pieces of the LDS read addresses
     const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
 
+    // ---- pipeline: K runs one tile ahead of V.  Entering iteration t, tile t's logits are
+    // in registers, K(t+1) and V(t) are in LDS.  The iteration issues the loads of K(t+2) and
+    // V(t+1), starts the matrix products of tile t+1's logits and, while they run, does the
+    // softmax of tile t on the vector unit; then O += V(t)^T P(t)^T.
+    f32x16 s_cur[2], s_nxt[2];
+    const bool wave_on = wave_has_rows;
+    if (nt > 0) {
+        load_k(0, 0);
+        load_v(0, 0);
+        if (nt > 1) load_k(1, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        if (wave_on && 0 <= kmax_wave) qk_tile(0, s_cur);
+    }
+
     for (int t = 0; t < nt; ++t) {
-        const int buf = t & 1;
-        const bool more = t + 1 < nt;
-        if (more) load_tile(t + 1);
-
         const int k0 = t * BN;
-        if (wave_has_rows && k0 <= kmax_wave) {
-            const unsigned char *ks = smem + buf * TILEB;
-            const unsigned char *vs = smem + (2 + buf) * TILEB;
+        if (t + 2 < nt) load_k(t + 2, t & 1);
+        if (t + 1 < nt) load_v(t + 1, (t + 1) & 1);
 
-            // ---- S^T = K Q^T : two 32-key blocks x 32 queries
-            f32x16 s[2];
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                s[mb] = (f32x16)(0.f);
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb) {
-                    const s16x8 a = *(const s16x8 *)(ks + k_lds_off<D>(mb * 32 + l32, 2 * kb + h));
-                    s[mb] = mfma32<DT>(a, qf[kb], s[mb]);
-                }
-            }
+        const bool act = wave_on && k0 <= kmax_wave;
+        const bool act_next = wave_on && (t + 1 < nt) && (k0 + BN <= kmax_wave);
+        if (act_next) qk_tile((t + 1) & 1, s_nxt);
+
+        if (act) {
+            const unsigned char *vs = smem + (2 + (t & 1)) * TILEB;
 
             // ---- mask only when the tile straddles the diagonal or the end of K
             const bool need_mask = (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
@@ -250,33 +294,35 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = k0 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (key > lim) s[mb][r] = -INFINITY;
+                        if (key > lim) s_cur[mb][r] = -INFINITY;
                     }
             }
 
             // ---- online softmax; the lane's 32 logits all belong to one query
-            float mx = s[0][0];
+            float mx = s_cur[0][0];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][r]);
-            mx = xhalf_max(mx);
-            const float m_new = fmaxf(m_run, mx);
-            const float mc = (m_new == -INFINITY) ? 0.f : m_new * p.c;
-            const float alpha = __builtin_amdgcn_exp2f(m_run * p.c - mc);
-            m_run = m_new;
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[mb][r]);
+            mx = xhalf_max(mx) * p.c;
+            const bool grow = mx > m_ref + RESCALE_TAU;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
+                m_ref = grow ? mx : m_ref;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+            }
             float rs = 0.f;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][r], p.c, -mc));
-                    s[mb][r] = e;
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[mb][r], p.c, -m_ref));
+                    s_cur[mb][r] = e;
                     rs += e;
                 }
-            l_run = l_run * alpha + rs;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+            l_run += rs;
 
             // ---- P^T fragments: 16-key step j takes logits registers 8*(j%2)..+7 of block j/2,
             // i.e. k-slot (h, v) of step j is key 16*j + 8*(v/4) + 4*h + v%4
@@ -285,7 +331,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
                 for (int v2 = 0; v2 < 4; ++v2) {
-                    const s16x2 pr = pack2<DT>(s[j >> 1][8 * (j & 1) + 2 * v2], s[j >> 1][8 * (j & 1) + 2 * v2 + 1]);
+                    const s16x2 pr = pack2<DT>(s_cur[j >> 1][8 * (j & 1) + 2 * v2], s_cur[j >> 1][8 * (j & 1) + 2 * v2 + 1]);
                     pf[j][2 * v2] = pr[0];
                     pf[j][2 * v2 + 1] = pr[1];
                 }
@@ -305,8 +351,10 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
                 }
             }
         }
+        s_cur[0] = s_nxt[0];
+        s_cur[1] = s_nxt[1];
 
-        if (more) store_tile(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of K(t+2), V(t+1) has landed
         __syncthreads();
     }
 
@@ -325,7 +373,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
                 *(s16x4 *)(op + db * 32 + 8 * g) = st;
             }
         if (h == 0)
-            p.lse[(size_t)bh * Nq + qrow] = l_tot > 0.f ? m_run * p.scale_abs + __logf(l_tot) : -INFINITY;
+            p.lse[(size_t)bh * Nq + qrow] = l_tot > 0.f ? (m_ref + __log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
     }
 }
 
