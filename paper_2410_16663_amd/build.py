@@ -14,7 +14,7 @@ HDR = os.path.join(os.path.dirname(HERE), "include", "fa.h")
 LIB = os.path.join(HERE, "libfa.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-shared", "-fPIC",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",

@@ -25,6 +25,9 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "../../include/fa.h"
 
 namespace {
@@ -119,13 +122,15 @@ __device__ __forceinline__ float xhalf_sum(float x) {
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane i's data lands at
-// lds_addr + 16*i.  Issued as inline asm so that the compiler does not put a vmcnt(0) wait
+// lds_addr + IMM + 16*i (the instruction's immediate offset applies to the global address
+// and to the LDS address alike).  Issued as inline asm so that the compiler does not put a vmcnt(0) wait
 // in front of every later LDS read (it cannot tell the buffers apart); the kernel waits
 // for vmcnt(0) itself before the barrier that publishes the tile.
+template <int IMM>
 __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
                  :
-                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "s"(lds_addr), "v"(voff), "s"(gbase), "n"(IMM)
                  : "memory", "m0");
 }
 
@@ -193,53 +198,62 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     // slot (row r, chunk c') fetches the global chunk that the swizzle maps there.
     constexpr int NI = TILEB / 1024 / NW;         // load instructions per wave per tile
     static_assert(TILEB % (1024 * NW) == 0, "tile must split evenly over the waves");
-    int k_src[NI], v_src[NI], ld_row[NI];         // per-lane source byte offsets inside a tile row block
+    constexpr int RPI = 1024 / ROWB;              // tile rows covered by one load instruction
+    // Instruction n of this wave fills LDS bytes [(wave*NI+n)*1024, +1024) of the tile: rows
+    // row0 + n*RPI + (lane*16)/ROWB.  The V swizzle does not depend on n; the K swizzle does.
+    const int ld_row0 = wave * NI * RPI + (lane * 16) / ROWB;
+    const int ld_cs = ((lane * 16) % ROWB) >> 4;
+    int k_voff[NI];                               // per-lane byte offset of the K chunk, relative to the tile
+    int v_voff;                                   // same for V, relative to row n*RPI of the tile
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-        const int slot = (wave * NI + n) * 1024 + lane * 16;   // LDS byte this lane fills
-        const int r = slot / ROWB, cs = (slot % ROWB) >> 4;
-        int ck, cv;
-        if constexpr (D == 128) {
-            ck = cs ^ (r & 15);
-            cv = cs ^ ((r & 3) << 2);
-        } else {
-            ck = cs ^ ((r >> 1) & 7);
-            cv = cs ^ (((r >> 1) & 1) << 2);
-        }
-        ld_row[n] = r;
-        k_src[n] = ck * 16;
-        v_src[n] = cv * 16;
+        const int r = ld_row0 + n * RPI;
+        const int ck = (D == 128) ? (ld_cs ^ (r & 15)) : (ld_cs ^ ((r >> 1) & 7));
+        k_voff[n] = ld_row0 * ROWB + ck * 16;
+    }
+    {
+        const int r = ld_row0;   // (r & 3) and ((r >> 1) & 1) are the same for every n: RPI is 4 or 8
+        const int cv = (D == 128) ? (ld_cs ^ ((r & 3) << 2)) : (ld_cs ^ (((r >> 1) & 1) << 2));
+        v_voff = ld_row0 * ROWB + cv * 16;
     }
     const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, smem));
     const unsigned char *kgb = (const unsigned char *)kg;
     const unsigned char *vgb = (const unsigned char *)vg;
-    auto load_k = [&](int t, int buf) {
+    // whole tiles take their per-lane offsets as they are (the tile start goes into the scalar
+    // base, the row step n*RPI into the instruction's immediate offset); the ragged last tile
+    // clamps its rows to the last key -- those rows are masked, they only have to be readable
+    auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k) {
+        constexpr bool IS_K = decltype(is_k)::value;
+        if (t * BN + BN <= Nk) {
+            const unsigned char *tb = gb + (size_t)t * TILEB;
+            [&]<int... Ns>(std::integer_sequence<int, Ns...>) {
+                (dma16_to_lds<Ns * 1024>(tb, (unsigned)(IS_K ? k_voff[Ns] : v_voff), lds_base + lds_off + wave * NI * 1024), ...);
+            }(std::make_integer_sequence<int, NI>{});
+        } else {
 #pragma unroll
-        for (int n = 0; n < NI; ++n) {
-            const int key = min(t * BN + ld_row[n], Nk - 1);   // rows past the end re-read the last key; they are masked
-            dma16_to_lds(kgb, (unsigned)(key * ROWB + k_src[n]), lds_base + buf * TILEB + (wave * NI + n) * 1024);
-        }
-    };
-    auto load_v = [&](int t, int buf) {
-#pragma unroll
-        for (int n = 0; n < NI; ++n) {
-            const int key = min(t * BN + ld_row[n], Nk - 1);
-            dma16_to_lds(vgb, (unsigned)(key * ROWB + v_src[n]), lds_base + (2 + buf) * TILEB + (wave * NI + n) * 1024);
-        }
-    };
-
-    // S^T = K Q^T for one 64-key tile held in K buffer `buf`
-    auto qk_tile = [&](int buf, f32x16 (&s)[2]) {
-        const unsigned char *ks = smem + buf * TILEB;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            s[mb] = (f32x16)(0.f);
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const s16x8 a = *(const s16x8 *)(ks + k_lds_off<D>(mb * 32 + l32, 2 * kb + h));
-                s[mb] = mfma32<DT>(a, qf[kb], s[mb]);
+            for (int n = 0; n < NI; ++n) {
+                const int key = min(t * BN + ld_row0 + n * RPI, Nk - 1);
+                const int src = (IS_K ? k_voff[n] : v_voff) - ld_row0 * ROWB;
+                dma16_to_lds<0>(gb, (unsigned)(key * ROWB + src), lds_base + lds_off + (wave * NI + n) * 1024);
             }
         }
+    };
+    auto load_k = [&](int t, int buf) { load_tile(kgb, t, buf * TILEB, std::true_type{}); };
+    auto load_v = [&](int t, int buf) { load_tile(vgb, t, (2 + buf) * TILEB, std::false_type{}); };
+
+    // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
+    auto k_frag = [&](const unsigned char *ks, int mb, int kb) -> s16x8 {
+        return *(const s16x8 *)(ks + k_lds_off<D>(mb * 32 + l32, 2 * kb + h));
+    };
+    // V^T fragment (j, db): rows = d db*32 + l32, k-slot (h, v) = key 16*j + 8*(v/4) + 4*h + v%4,
+    // fetched with two transposing reads of 4 keys x 16 d per 16-lane group.
+    const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
+    auto v_frag = [&](const unsigned char *vs, int j, int db) -> s16x8 {
+        const int row = 16 * j + 4 * h + vi;
+        const int bcol = db * 64 + g2 * 32 + vc * 8;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vs + v_lds_off<D>(row, bcol)));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vs + v_lds_off<D>(row + 8, bcol)));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
     f32x16 oacc[DB];
@@ -254,108 +268,157 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     float m_ref = -1e30f;
     float l_run = 0.f;         // this half-wave's share of the row sum, relative to m_ref
 
-    // per-lane pieces of the LDS read addresses
-    const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
+    // mask + row maximum of 4 logits registers (unit u of 8) of a tile starting at key k0
+    auto max_unit = [&](auto mask_c, f32x16 (&s)[2], int u, int k0, int lim, float &mx) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        const int mb = u >> 2, r0 = (u & 3) * 4;
+        if constexpr (MASK) {
+#pragma unroll
+            for (int r = r0; r < r0 + 4; ++r) {
+                const int key = k0 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (key > lim) s[mb][r] = -INFINITY;
+            }
+        }
+        mx = fmaxf(fmaxf(mx, s[mb][r0]), s[mb][r0 + 1]);
+        mx = fmaxf(fmaxf(mx, s[mb][r0 + 2]), s[mb][r0 + 3]);
+    };
 
-    // ---- pipeline: K runs one tile ahead of V.  Entering iteration t, tile t's logits are
-    // in registers, K(t+1) and V(t) are in LDS.  The iteration issues the loads of K(t+2) and
-    // V(t+1), starts the matrix products of tile t+1's logits and, while they run, does the
-    // softmax of tile t on the vector unit; then O += V(t)^T P(t)^T.
-    f32x16 s_cur[2], s_nxt[2];
-    const bool wave_on = wave_has_rows;
+    auto tile_masked = [&](int t) -> bool {
+        const int k0 = t * BN;
+        return (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
+    };
+
+    // ---- one tile of the pipeline, for this wave, as an explicit instruction schedule.
+    // Entering: tile t's logits are in `sc` and their scaled row maximum in `mx`; K(t+1) and
+    // V(t) are in LDS.  The step is a sequence of NM matrix instructions -- first the 2*KB of
+    // tile t+1's logits S^T = K Q^T, then the 4*DB of O^T += V(t)^T P(t)^T -- and every matrix
+    // instruction carries, in its shadow, a share of the vector work: first the 16 groups of
+    // two exponentials of tile t (each yields one packed pair of P), then mask and row maximum
+    // of the new logits.  Operand fragments are read from LDS LA instructions ahead.  The
+    // scheduling barriers pin this order; registers and wait counts are left to the compiler.
+    // The row maximum of the new logits is taken unmasked; a tile that needs the mask applies
+    // it, and recomputes its row maximum, in a short pre-pass of its own step (once per wave
+    // in a causal run).  The wave's last tile runs the same schedule: its "next logits" are
+    // computed from whatever the K buffer holds and never used.
+    constexpr int NQK = 2 * KB, NPV = 4 * DB, NM = NQK + NPV;
+    constexpr int E_SPAN = NM * 23 / 32;     // the exponentials ride on the first E_SPAN matrix instructions
+    constexpr int LA = 2;   // 3 costs a handful of spills at D = 128
+    auto tile_step = [&](auto par_c, int t, f32x16 (&sc)[2], f32x16 (&sn)[2], float &mx) {
+        constexpr int PAR = decltype(par_c)::value;
+        const unsigned char *ksn = smem + (PAR ^ 1) * TILEB;   // K(t+1)
+        const unsigned char *vs = smem + (2 + PAR) * TILEB;     // V(t)
+
+        if (tile_masked(t)) {
+            int lim = Nk - 1;
+            if (CAUSAL) lim = min(lim, qrow + off);
+            float mm = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) max_unit(std::true_type{}, sc, u, t * BN, lim, mm);
+            mx = xhalf_max(mm) * p.c;
+        }
+
+        // rare: move the exponent reference up and rescale what has been accumulated
+        const bool grow = mx > m_ref + RESCALE_TAU;
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
+            m_ref = grow ? mx : m_ref;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+        }
+        const float nm = -m_ref;
+        float rs0 = 0.f, rs1 = 0.f;
+        s16x8 pf[4];
+        // exponentials of logits registers (j, v2): two elements -> one packed pair of P^T
+        auto exp_group = [&](int g) {
+            const int j = g >> 2, v2 = g & 3;
+            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j >> 1][8 * (j & 1) + 2 * v2], p.c, nm));
+            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j >> 1][8 * (j & 1) + 2 * v2 + 1], p.c, nm));
+            rs0 += e0;
+            rs1 += e1;
+            const s16x2 pr = pack2<DT>(e0, e1);
+            pf[j][2 * v2] = pr[0];
+            pf[j][2 * v2 + 1] = pr[1];
+        };
+
+        {
+            float mxn = -INFINITY;
+            s16x8 fr[NM];
+            auto read_frag = [&](int i) {
+                if (i < NQK) fr[i] = k_frag(ksn, i / KB, i % KB);
+                else fr[i] = v_frag(vs, (i - NQK) / DB, (i - NQK) % DB);
+            };
+#pragma unroll
+            for (int i = 0; i < LA; ++i) read_frag(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                if (i + LA < NM) read_frag(i + LA);
+                if (i < NQK) {
+                    const int mb = i / KB, kb = i % KB;
+                    if (kb == 0) sn[mb] = (f32x16)(0.f);
+                    sn[mb] = mfma32<DT>(fr[i], qf[kb], sn[mb]);
+                } else {
+                    const int j = (i - NQK) / DB, db = (i - NQK) % DB;
+                    oacc[db] = mfma32<DT>(fr[i], pf[j], oacc[db]);
+                }
+#pragma unroll
+                for (int g = 0; g < 16; ++g)
+                    if (g * E_SPAN / 16 == i) exp_group(g);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (E_SPAN + u * (NM - 1 - E_SPAN) / 8 == i)
+                        max_unit(std::false_type{}, sn, u, 0, 0, mxn);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            mx = xhalf_max(mxn) * p.c;
+        }
+        l_run += rs0 + rs1;
+    };
+
+    // ---- workgroup pipeline: K runs one tile ahead of V.  Iteration t issues the loads of
+    // K(t+2) and V(t+1), runs the wave's tile step, then waits for its loads and meets the
+    // other waves at the barrier that publishes them.
+    const int n_act = (wave_has_rows && kmax_wave >= 0) ? kmax_wave / BN + 1 : 0;   // tiles this wave works on
+    f32x16 s_a[2], s_b[2];
+    float mx_run = -INFINITY;
     if (nt > 0) {
         load_k(0, 0);
         load_v(0, 0);
         if (nt > 1) load_k(1, 1);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
-        if (wave_on && 0 <= kmax_wave) qk_tile(0, s_cur);
+        if (n_act > 0) {
+            // logits and row maximum of tile 0, not overlapped with anything
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                s_a[mb] = (f32x16)(0.f);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) s_a[mb] = mfma32<DT>(k_frag(smem, mb, kb), qf[kb], s_a[mb]);
+            }
+            float m0 = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) max_unit(std::false_type{}, s_a, u, 0, 0, m0);
+            mx_run = xhalf_max(m0) * p.c;
+        }
+        // tile 0's K buffer is the first one the loop refills: every wave must be done reading it
+        __syncthreads();
     }
 
-    for (int t = 0; t < nt; ++t) {
-        const int k0 = t * BN;
-        if (t + 2 < nt) load_k(t + 2, t & 1);
-        if (t + 1 < nt) load_v(t + 1, (t + 1) & 1);
-
-        const bool act = wave_on && k0 <= kmax_wave;
-        const bool act_next = wave_on && (t + 1 < nt) && (k0 + BN <= kmax_wave);
-        if (act_next) qk_tile((t + 1) & 1, s_nxt);
-
-        if (act) {
-            const unsigned char *vs = smem + (2 + (t & 1)) * TILEB;
-
-            // ---- mask only when the tile straddles the diagonal or the end of K
-            const bool need_mask = (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
-            if (need_mask) {
-                int lim = Nk - 1;
-                if (CAUSAL) lim = min(lim, qrow + off);
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = k0 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (key > lim) s_cur[mb][r] = -INFINITY;
-                    }
-            }
-
-            // ---- online softmax; the lane's 32 logits all belong to one query
-            float mx = s_cur[0][0];
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[mb][r]);
-            mx = xhalf_max(mx) * p.c;
-            const bool grow = mx > m_ref + RESCALE_TAU;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
-                m_ref = grow ? mx : m_ref;
-                l_run *= alpha;
-#pragma unroll
-                for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
-            }
-            float rs = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[mb][r], p.c, -m_ref));
-                    s_cur[mb][r] = e;
-                    rs += e;
-                }
-            l_run += rs;
-
-            // ---- P^T fragments: 16-key step j takes logits registers 8*(j%2)..+7 of block j/2,
-            // i.e. k-slot (h, v) of step j is key 16*j + 8*(v/4) + 4*h + v%4
-            s16x8 pf[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                for (int v2 = 0; v2 < 4; ++v2) {
-                    const s16x2 pr = pack2<DT>(s_cur[j >> 1][8 * (j & 1) + 2 * v2], s_cur[j >> 1][8 * (j & 1) + 2 * v2 + 1]);
-                    pf[j][2 * v2] = pr[0];
-                    pf[j][2 * v2 + 1] = pr[1];
-                }
-            }
-
-            // ---- O^T += V^T P^T : A operand rows are d, k-slots match the P^T fragments
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int row = 16 * j + 4 * h + vi;
-                    const int bcol = db * 64 + g2 * 32 + vc * 8;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vs + v_lds_off<D>(row, bcol)));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vs + v_lds_off<D>(row + 8, bcol)));
-                    const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    oacc[db] = mfma32<DT>(a, pf[j], oacc[db]);
-                }
-            }
-        }
-        s_cur[0] = s_nxt[0];
-        s_cur[1] = s_nxt[1];
-
+    using std::integral_constant;
+    auto iteration = [&](auto par_c, int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+        constexpr int PAR = decltype(par_c)::value;
+        if (t + 2 < nt) load_k(t + 2, PAR);
+        if (t + 1 < nt) load_v(t + 1, PAR ^ 1);
+        if (t < n_act) tile_step(par_c, t, sc, sn, mx_run);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of K(t+2), V(t+1) has landed
         __syncthreads();
+    };
+    // iterations come in pairs so that the two logits buffers swap roles without copies; an
+    // odd tile count is rounded up (the extra iteration has no tile and only meets the barrier)
+    for (int t = 0; t < nt; t += 2) {
+        iteration(integral_constant<int, 0>{}, t, s_a, s_b);
+        iteration(integral_constant<int, 1>{}, t + 1, s_b, s_a);
     }
 
     // ---- epilogue: combine the two half-wave sums, normalise, store
