@@ -19,7 +19,7 @@ extern "C" {
 /* error codes (0 = success); every argument error is detected on the host before any HIP call */
 #define FA_OK            0
 #define FA_ERR_NULL     -1 /* a required pointer is NULL */
-#define FA_ERR_SHAPE    -2 /* B, H, Nq or Nk <= 0, or a tensor/grid too large to index */
+#define FA_ERR_SHAPE    -2 /* B, H, Nq or Nk <= 0, or a tensor/grid too large to index (one head of K/V must stay under 2 GiB) */
 #define FA_ERR_HEADDIM  -3 /* D is not 64 or 128 */
 #define FA_ERR_DTYPE    -4 /* dtype is not FA_DTYPE_F16 or FA_DTYPE_BF16 */
 #define FA_ERR_SCALE    -5 /* scale is NaN or infinite */
@@ -63,6 +63,35 @@ extern "C" {
 int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
            int B, int H, int Nq, int Nk, int D, float scale, int causal, int dtype,
            void *stream);
+
+/*
+ * Work decomposition fa_fwd uses for a problem (section 4.1: tiles above the diagonal are
+ * skipped; appendix A: the work is split over the sequence as well as over batch and heads).
+ * FA_MODE_SPLIT: a workgroup owns 128 query rows and its two wave groups take alternate
+ * 64-key tiles; FA_MODE_WIDE: a workgroup owns 256 query rows and all its waves walk the same
+ * tiles.  fa_fwd picks WIDE when B*H*ceil(Nq/256) >= 256, else SPLIT; the environment
+ * variable FA_FWD_MODE=split|wide overrides the choice (for tests and tuning).
+ */
+#define FA_MODE_SPLIT 0
+#define FA_MODE_WIDE  1
+
+typedef struct fa_plan {
+    int mode;                 /* FA_MODE_SPLIT or FA_MODE_WIDE */
+    int block_m;              /* query rows per workgroup */
+    int block_n;              /* keys per tile */
+    int threads;              /* threads per workgroup */
+    int grid;                 /* workgroups launched (work items rounded up to a multiple of 8) */
+    int lds_bytes;            /* LDS per workgroup */
+    long long work_items;     /* B * H * ceil(Nq / block_m) */
+    long long tiles_visited;  /* (query block, key tile) pairs the kernel walks: masked-out tiles are skipped */
+    long long tiles_total;    /* the same count without skipping */
+} fa_plan_t;
+
+/*
+ * fa_fwd_plan -- host-only: fills *plan (caller-owned, HOST pointer) for the given problem
+ * without touching the GPU.  Same shape checks and error codes as fa_fwd.
+ */
+int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_plan_t *plan);
 
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);

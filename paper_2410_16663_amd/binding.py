@@ -22,11 +22,21 @@ FA_ERR_ALIGN = -6
 FA_ERR_LAUNCH = -7
 FA_DTYPE_F16 = 0
 FA_DTYPE_BF16 = 1
+FA_MODE_SPLIT = 0
+FA_MODE_WIDE = 1
 
 # every symbol include/fa.h declares
-EXPORTS = ("fa_fwd", "fa_strerror", "fa_version", "fa_last_hip_error")
+EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_strerror", "fa_version", "fa_last_hip_error")
 
 _lib = None
+
+
+class FaPlan(ctypes.Structure):
+    """fa_plan_t of include/fa.h."""
+    _fields_ = [("mode", ctypes.c_int), ("block_m", ctypes.c_int), ("block_n", ctypes.c_int),
+                ("threads", ctypes.c_int), ("grid", ctypes.c_int), ("lds_bytes", ctypes.c_int),
+                ("work_items", ctypes.c_longlong), ("tiles_visited", ctypes.c_longlong),
+                ("tiles_total", ctypes.c_longlong)]
 
 
 class FaError(RuntimeError):
@@ -48,6 +58,8 @@ def load() -> ctypes.CDLL:
         lib.fa_fwd.restype = ctypes.c_int
         lib.fa_fwd.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
             ctypes.c_float, ctypes.c_int, ctypes.c_int, vp]
+        lib.fa_fwd_plan.restype = ctypes.c_int
+        lib.fa_fwd_plan.argtypes = [ctypes.c_int] * 7 + [ctypes.POINTER(FaPlan)]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -79,6 +91,15 @@ def fa_fwd(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream=0) -> 
     rc = fa_fwd_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream)
     if rc != FA_OK:
         raise FaError(rc)
+
+
+def fa_fwd_plan(B, H, Nq, Nk, D, causal, dtype) -> FaPlan:
+    """fa_fwd_plan of include/fa.h (host only, no GPU needed); raises FaError on a bad shape."""
+    plan = FaPlan()
+    rc = load().fa_fwd_plan(int(B), int(H), int(Nq), int(Nk), int(D), int(causal), int(dtype), ctypes.byref(plan))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return plan
 
 
 def fa_strerror(code: int) -> str:

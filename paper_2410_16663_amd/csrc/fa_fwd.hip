@@ -9,7 +9,15 @@
 // per-element predicate computed from indices -- no mask tensor exists.
 //
 // gfx950 mapping (this file's own design):
-//  * one wavefront owns 32 query rows; a workgroup is NW wavefronts = 32*NW rows.
+//  * one wavefront owns 32 query rows.  A workgroup is 8 wavefronts on 128 query rows: two
+//    groups of four, both groups on the same rows; group 0 takes the even 64-key tiles and
+//    group 1 the odd ones, and their partial results (accumulator, exponent reference, row
+//    sum) are merged through LDS at the end.  Each SIMD thus holds one wavefront of each
+//    group.  A wavefront cannot issue vector work while its own matrix instruction runs, so
+//    overlap of the matrix and vector units comes from the two groups being in opposite
+//    phases: while one group runs its matrix cluster (Q K^T of its tile and P V of its
+//    previous tile) the other runs its vector cluster (softmax of its tile); workgroup
+//    barriers between the clusters keep the two in step.
 //  * logits are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: keys on the
 //    M side (A operand, read from LDS with ds_read_b128), queries on the N side (B
 //    operand, held in registers for the whole kernel).  A lane then owns ONE query
@@ -19,11 +27,13 @@
 //    round trip -- the MFMA counterpart of the paper's appendix-B layout converter).
 //  * V^T fragments come straight out of the row-major V tile with the transposing LDS
 //    read ds_read_b64_tr_b16.
-//  * K and V tiles (64 keys) are double-buffered in LDS; the next tile's global loads
-//    are in flight while the current one is consumed.
+//  * K and V tiles (64 keys) go from global memory straight into LDS (global_load_lds),
+//    double-buffered per group, issued two clusters before they are needed.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include <type_traits>
 #include <utility>
@@ -53,7 +63,6 @@ struct FaParams {
     int nwork;      // B*H*nqt
     int per_xcd;    // ceil(nwork / 8)
     float c;        // |scale| * log2(e), or 1 when scale == 0
-    float scale_abs;
     int qmode;      // 0: use q as is, 1: negate q (scale < 0), 2: zero q (scale == 0)
 };
 
@@ -126,6 +135,14 @@ __device__ __forceinline__ float xhalf_sum(float x) {
 // and to the LDS address alike).  Issued as inline asm so that the compiler does not put a vmcnt(0) wait
 // in front of every later LDS read (it cannot tell the buffers apart); the kernel waits
 // for vmcnt(0) itself before the barrier that publishes the tile.
+// a pointer that is the same in every lane, moved to scalar registers for the compiler's benefit
+__device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char *p) {
+    const uint64_t a = (uint64_t)(uintptr_t)p;
+    const uint64_t lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    const uint64_t hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
+    return (const unsigned char *)(uintptr_t)(lo | (hi << 32));
+}
+
 template <int IMM>
 __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
@@ -134,23 +151,32 @@ __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, u
                  : "memory", "m0");
 }
 
-template <int DT, int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
-    constexpr int NT = NW * 64;
-    constexpr int BM = NW * 32;
-    constexpr int KB = D / 16;   // k-steps of the first product
-    constexpr int DB = D / 32;   // 32-row blocks of O^T
+// WIDE = false: the two groups of four waves work on the SAME 128 query rows and take
+//   alternate key tiles (group 0 the even ones, group 1 the odd ones), each group loading its
+//   own tiles; their partial results are merged at the end.  Halves the longest chain of
+//   tiles per workgroup: the shape for short sequences, where workgroups are few and uneven.
+// WIDE = true: the eight waves work on 256 different query rows and all walk the same key
+//   tiles, loaded once for the whole workgroup.  Halves the K/V traffic into LDS per unit of
+//   work: the shape for long sequences.
+template <int DT, int D, bool CAUSAL, bool WIDE>
+__global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
+    constexpr int NWL = WIDE ? 8 : 4;             // waves that load one tile together
+    constexpr int BM = WIDE ? 256 : 128;          // query rows per workgroup
+    constexpr int TSTEP = WIDE ? 1 : 2;           // a group's consecutive tiles are TSTEP apart
+    constexpr int KB = D / 16;                    // k-steps of the first product
+    constexpr int DB = D / 32;                    // 32-row blocks of O^T
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;
-    constexpr int CPR = D / 8;   // 16-byte chunks per row
-    constexpr int PER = BN * CPR / NT;
-    static_assert(PER >= 1 && BN * CPR % NT == 0, "tile must split evenly over the threads");
+    constexpr int GROUPB = 4 * TILEB;             // one set of buffers: K0 K1 V0 V1
+    constexpr int NSETS = WIDE ? 1 : 2;           // split mode: one set per group
 
-    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILEB];  // K0 K1 V0 V1
+    __shared__ __attribute__((aligned(16))) unsigned char smem[NSETS * GROUPB];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = WIDE ? 0 : (wave >> 2);       // split mode: 0 = even tiles, 1 = odd tiles
+    const int wq = WIDE ? wave : (wave & 3);      // which 32 query rows, and which share of the loads
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
@@ -164,20 +190,23 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
 
     const int Nq = p.Nq, Nk = p.Nk;
     const int off = Nk - Nq;
-    const int q_wave = qt * BM + wave * 32;       // first query row of this wave
+    const int q_wave = qt * BM + wq * 32;         // first query row of this wave
     const int qrow = q_wave + l32;                // this lane's query row
-    const bool wave_has_rows = q_wave < Nq;
 
     int kmax_wg = Nk - 1, kmax_wave = Nk - 1;     // last key index any row may see
     if (CAUSAL) {
         kmax_wg = min(Nk - 1, min(qt * BM + BM - 1, Nq - 1) + off);
         kmax_wave = min(Nk - 1, min(q_wave + 31, Nq - 1) + off);
     }
-    const int nt = kmax_wg >= 0 ? kmax_wg / BN + 1 : 0;
+    const int nt = kmax_wg >= 0 ? kmax_wg / BN + 1 : 0;     // 64-key tiles the workgroup walks
+    // group-local tile j is global tile TSTEP*j + grp
+    const int nj_loop = (nt + TSTEP - 1) / TSTEP;            // tiles of group 0 (>= those of group 1)
+    int n_act = 0;                                           // group tiles this wave works on
+    if (q_wave < Nq && kmax_wave >= 0 && kmax_wave / BN >= grp) n_act = (kmax_wave / BN - grp) / TSTEP + 1;
 
     const size_t kv_head = (size_t)bh * Nk * D;
-    const uint16_t *kg = p.k + kv_head;
-    const uint16_t *vg = p.v + kv_head;
+    const unsigned char *kgb = (const unsigned char *)(p.k + kv_head);
+    const unsigned char *vgb = (const unsigned char *)(p.v + kv_head);
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds d = 16*kb + 8*h + 0..7 of its row
     s16x8 qf[KB];
@@ -195,13 +224,14 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- K/V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per
     // lane, no staging registers).  One such instruction fills 1 KiB of LDS contiguously in
     // lane order, so the bank swizzle is applied on the global side: the lane that owns LDS
-    // slot (row r, chunk c') fetches the global chunk that the swizzle maps there.
-    constexpr int NI = TILEB / 1024 / NW;         // load instructions per wave per tile
-    static_assert(TILEB % (1024 * NW) == 0, "tile must split evenly over the waves");
+    // slot (row r, chunk c') fetches the global chunk that the swizzle maps there.  The NWL
+    // waves that share a set of buffers load its tiles together.
+    constexpr int NI = TILEB / 1024 / NWL;        // load instructions per wave per tile
+    static_assert(TILEB % (1024 * NWL) == 0, "tile must split evenly over the waves");
     constexpr int RPI = 1024 / ROWB;              // tile rows covered by one load instruction
-    // Instruction n of this wave fills LDS bytes [(wave*NI+n)*1024, +1024) of the tile: rows
+    // Instruction n of this wave fills LDS bytes [(wq*NI+n)*1024, +1024) of the tile: rows
     // row0 + n*RPI + (lane*16)/ROWB.  The V swizzle does not depend on n; the K swizzle does.
-    const int ld_row0 = wave * NI * RPI + (lane * 16) / ROWB;
+    const int ld_row0 = wq * NI * RPI + (lane * 16) / ROWB;
     const int ld_cs = ((lane * 16) % ROWB) >> 4;
     int k_voff[NI];                               // per-lane byte offset of the K chunk, relative to the tile
     int v_voff;                                   // same for V, relative to row n*RPI of the tile
@@ -216,39 +246,39 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
         const int cv = (D == 128) ? (ld_cs ^ ((r & 3) << 2)) : (ld_cs ^ (((r >> 1) & 1) << 2));
         v_voff = ld_row0 * ROWB + cv * 16;
     }
-    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, smem));
-    const unsigned char *kgb = (const unsigned char *)kg;
-    const unsigned char *vgb = (const unsigned char *)vg;
+    unsigned char *gsm = smem + grp * GROUPB;     // this group's buffers
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, gsm));
     // whole tiles take their per-lane offsets as they are (the tile start goes into the scalar
     // base, the row step n*RPI into the instruction's immediate offset); the ragged last tile
     // clamps its rows to the last key -- those rows are masked, they only have to be readable
-    auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k) {
+    auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k) __attribute__((always_inline)) {
         constexpr bool IS_K = decltype(is_k)::value;
         if (t * BN + BN <= Nk) {
-            const unsigned char *tb = gb + (size_t)t * TILEB;
+            const unsigned char *tb = uniform_ptr(gb + (size_t)t * TILEB);
             [&]<int... Ns>(std::integer_sequence<int, Ns...>) {
-                (dma16_to_lds<Ns * 1024>(tb, (unsigned)(IS_K ? k_voff[Ns] : v_voff), lds_base + lds_off + wave * NI * 1024), ...);
+                (dma16_to_lds<Ns * 1024>(tb, (unsigned)(IS_K ? k_voff[Ns] : v_voff), lds_base + lds_off + wq * NI * 1024), ...);
             }(std::make_integer_sequence<int, NI>{});
         } else {
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
                 const int key = min(t * BN + ld_row0 + n * RPI, Nk - 1);
                 const int src = (IS_K ? k_voff[n] : v_voff) - ld_row0 * ROWB;
-                dma16_to_lds<0>(gb, (unsigned)(key * ROWB + src), lds_base + lds_off + (wave * NI + n) * 1024);
+                dma16_to_lds<0>(uniform_ptr(gb), (unsigned)(key * ROWB + src), lds_base + lds_off + (wq * NI + n) * 1024);
             }
         }
     };
-    auto load_k = [&](int t, int buf) { load_tile(kgb, t, buf * TILEB, std::true_type{}); };
-    auto load_v = [&](int t, int buf) { load_tile(vgb, t, (2 + buf) * TILEB, std::false_type{}); };
+    // group tile j -> buffer j & 1
+    auto load_k = [&](int j) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, (j & 1) * TILEB, std::true_type{}); };
+    auto load_v = [&](int j) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (2 + (j & 1)) * TILEB, std::false_type{}); };
 
     // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
-    auto k_frag = [&](const unsigned char *ks, int mb, int kb) -> s16x8 {
+    auto k_frag = [&](const unsigned char *ks, int mb, int kb) __attribute__((always_inline)) -> s16x8 {
         return *(const s16x8 *)(ks + k_lds_off<D>(mb * 32 + l32, 2 * kb + h));
     };
     // V^T fragment (j, db): rows = d db*32 + l32, k-slot (h, v) = key 16*j + 8*(v/4) + 4*h + v%4,
     // fetched with two transposing reads of 4 keys x 16 d per 16-lane group.
     const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
-    auto v_frag = [&](const unsigned char *vs, int j, int db) -> s16x8 {
+    auto v_frag = [&](const unsigned char *vs, int j, int db) __attribute__((always_inline)) -> s16x8 {
         const int row = 16 * j + 4 * h + vi;
         const int bcol = db * 64 + g2 * 32 + vc * 8;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vs + v_lds_off<D>(row, bcol)));
@@ -268,157 +298,153 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     float m_ref = -1e30f;
     float l_run = 0.f;         // this half-wave's share of the row sum, relative to m_ref
 
-    // mask + row maximum of 4 logits registers (unit u of 8) of a tile starting at key k0
-    auto max_unit = [&](auto mask_c, f32x16 (&s)[2], int u, int k0, int lim, float &mx) {
-        constexpr bool MASK = decltype(mask_c)::value;
-        const int mb = u >> 2, r0 = (u & 3) * 4;
-        if constexpr (MASK) {
-#pragma unroll
-            for (int r = r0; r < r0 + 4; ++r) {
-                const int key = k0 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (key > lim) s[mb][r] = -INFINITY;
-            }
-        }
-        mx = fmaxf(fmaxf(mx, s[mb][r0]), s[mb][r0 + 1]);
-        mx = fmaxf(fmaxf(mx, s[mb][r0 + 2]), s[mb][r0 + 3]);
-    };
+    f32x16 sreg[2];            // logits of the current tile (two 32-key blocks)
+    s16x8 pf[4];               // its exponentials, packed, as B operands of the four 16-key steps
 
-    auto tile_masked = [&](int t) -> bool {
-        const int k0 = t * BN;
-        return (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
-    };
+#ifndef FA_LA
+#define FA_LA 2
+#endif
+    constexpr int LA = FA_LA;  // operand fragments are read this many matrix instructions ahead
 
-    // ---- one tile of the pipeline, for this wave, as an explicit instruction schedule.
-    // Entering: tile t's logits are in `sc` and their scaled row maximum in `mx`; K(t+1) and
-    // V(t) are in LDS.  The step is a sequence of NM matrix instructions -- first the 2*KB of
-    // tile t+1's logits S^T = K Q^T, then the 4*DB of O^T += V(t)^T P(t)^T -- and every matrix
-    // instruction carries, in its shadow, a share of the vector work: first the 16 groups of
-    // two exponentials of tile t (each yields one packed pair of P), then mask and row maximum
-    // of the new logits.  Operand fragments are read from LDS LA instructions ahead.  The
-    // scheduling barriers pin this order; registers and wait counts are left to the compiler.
-    // The row maximum of the new logits is taken unmasked; a tile that needs the mask applies
-    // it, and recomputes its row maximum, in a short pre-pass of its own step (once per wave
-    // in a causal run).  The wave's last tile runs the same schedule: its "next logits" are
-    // computed from whatever the K buffer holds and never used.
-    constexpr int NQK = 2 * KB, NPV = 4 * DB, NM = NQK + NPV;
-    constexpr int E_SPAN = NM * 23 / 32;     // the exponentials ride on the first E_SPAN matrix instructions
-    constexpr int LA = 2;   // 3 costs a handful of spills at D = 128
-    auto tile_step = [&](auto par_c, int t, f32x16 (&sc)[2], f32x16 (&sn)[2], float &mx) {
+    // ---- S^T = K(j) Q^T for group tile j (K buffer PAR = j & 1)
+    auto qk_cluster = [&](auto par_c) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_c)::value;
-        const unsigned char *ksn = smem + (PAR ^ 1) * TILEB;   // K(t+1)
-        const unsigned char *vs = smem + (2 + PAR) * TILEB;     // V(t)
-
-        if (tile_masked(t)) {
-            int lim = Nk - 1;
-            if (CAUSAL) lim = min(lim, qrow + off);
-            float mm = -INFINITY;
+        const unsigned char *ks = gsm + PAR * TILEB;
+        s16x8 fr[2 * KB];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) max_unit(std::true_type{}, sc, u, t * BN, lim, mm);
-            mx = xhalf_max(mm) * p.c;
-        }
-
-        // rare: move the exponent reference up and rescale what has been accumulated
-        const bool grow = mx > m_ref + RESCALE_TAU;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-            const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
-            m_ref = grow ? mx : m_ref;
-            l_run *= alpha;
+        for (int i = 0; i < LA; ++i) fr[i] = k_frag(ks, i & 1, i >> 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
-        }
-        const float nm = -m_ref;
-        float rs0 = 0.f, rs1 = 0.f;
-        s16x8 pf[4];
-        // exponentials of logits registers (j, v2): two elements -> one packed pair of P^T
-        auto exp_group = [&](int g) {
-            const int j = g >> 2, v2 = g & 3;
-            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j >> 1][8 * (j & 1) + 2 * v2], p.c, nm));
-            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j >> 1][8 * (j & 1) + 2 * v2 + 1], p.c, nm));
-            rs0 += e0;
-            rs1 += e1;
-            const s16x2 pr = pack2<DT>(e0, e1);
-            pf[j][2 * v2] = pr[0];
-            pf[j][2 * v2 + 1] = pr[1];
-        };
-
-        {
-            float mxn = -INFINITY;
-            s16x8 fr[NM];
-            auto read_frag = [&](int i) {
-                if (i < NQK) fr[i] = k_frag(ksn, i / KB, i % KB);
-                else fr[i] = v_frag(vs, (i - NQK) / DB, (i - NQK) % DB);
-            };
-#pragma unroll
-            for (int i = 0; i < LA; ++i) read_frag(i);
+        for (int i = 0; i < 2 * KB; ++i) {      // the two key blocks alternate: independent accumulators
+            if (i + LA < 2 * KB) fr[i + LA] = k_frag(ks, (i + LA) & 1, (i + LA) >> 1);
+            const int mb = i & 1, kb = i >> 1;
+            if (kb == 0) sreg[mb] = (f32x16)(0.f);
+            sreg[mb] = mfma32<DT>(fr[i], qf[kb], sreg[mb]);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < NM; ++i) {
-                if (i + LA < NM) read_frag(i + LA);
-                if (i < NQK) {
-                    const int mb = i / KB, kb = i % KB;
-                    if (kb == 0) sn[mb] = (f32x16)(0.f);
-                    sn[mb] = mfma32<DT>(fr[i], qf[kb], sn[mb]);
-                } else {
-                    const int j = (i - NQK) / DB, db = (i - NQK) % DB;
-                    oacc[db] = mfma32<DT>(fr[i], pf[j], oacc[db]);
-                }
-#pragma unroll
-                for (int g = 0; g < 16; ++g)
-                    if (g * E_SPAN / 16 == i) exp_group(g);
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (E_SPAN + u * (NM - 1 - E_SPAN) / 8 == i)
-                        max_unit(std::false_type{}, sn, u, 0, 0, mxn);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            mx = xhalf_max(mxn) * p.c;
         }
-        l_run += rs0 + rs1;
+    };
+    // ---- O^T += V(j)^T P(j)^T (V buffer PAR = j & 1)
+    auto pv_cluster = [&](auto par_c) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_c)::value;
+        const unsigned char *vs = gsm + (2 + PAR) * TILEB;
+        s16x8 fr[4 * DB];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) fr[i] = v_frag(vs, i / DB, i % DB);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4 * DB; ++i) {
+            if (i + LA < 4 * DB) fr[i + LA] = v_frag(vs, (i + LA) / DB, (i + LA) % DB);
+            oacc[i % DB] = mfma32<DT>(fr[i], pf[i / DB], oacc[i % DB]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
-    // ---- workgroup pipeline: K runs one tile ahead of V.  Iteration t issues the loads of
-    // K(t+2) and V(t+1), runs the wave's tile step, then waits for its loads and meets the
-    // other waves at the barrier that publishes them.
-    const int n_act = (wave_has_rows && kmax_wave >= 0) ? kmax_wave / BN + 1 : 0;   // tiles this wave works on
-    f32x16 s_a[2], s_b[2];
-    float mx_run = -INFINITY;
-    if (nt > 0) {
-        load_k(0, 0);
-        load_v(0, 0);
-        if (nt > 1) load_k(1, 1);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __syncthreads();
-        if (n_act > 0) {
-            // logits and row maximum of tile 0, not overlapped with anything
+    // ---- softmax of group tile j: logits in sreg -> packed exponentials in pf, running sums
+    auto softmax_cluster = [&](int j) __attribute__((always_inline)) {
+        {
+            const int k0 = (TSTEP * j + grp) * BN;
+            // mask only when the tile straddles the diagonal or the end of K
+            const bool need_mask = (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
+            if (need_mask) {
+                int lim = Nk - 1;
+                if (CAUSAL) lim = min(lim, qrow + off);
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                s_a[mb] = (f32x16)(0.f);
+                for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) s_a[mb] = mfma32<DT>(k_frag(smem, mb, kb), qf[kb], s_a[mb]);
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = k0 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (key > lim) sreg[mb][r] = -INFINITY;
+                    }
             }
-            float m0 = -INFINITY;
+            // the lane's 32 logits all belong to one query
+            float mx = sreg[0][0];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) max_unit(std::false_type{}, s_a, u, 0, 0, m0);
-            mx_run = xhalf_max(m0) * p.c;
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sreg[mb][r]);
+            mx = xhalf_max(mx) * p.c;
+            // rare: move the exponent reference up and rescale what has been accumulated
+            const bool grow = mx > m_ref + RESCALE_TAU;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
+                m_ref = grow ? mx : m_ref;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+            }
+            const float nm = -m_ref;
+            float rs0 = 0.f, rs1 = 0.f;
+            // P^T fragments: 16-key step jj takes logits registers 8*(jj%2)..+7 of block jj/2,
+            // i.e. k-slot (h, v) of step jj is key 16*jj + 8*(v/4) + 4*h + v%4
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int v2 = 0; v2 < 4; ++v2) {
+                    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2], p.c, nm));
+                    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2 + 1], p.c, nm));
+                    rs0 += e0;
+                    rs1 += e1;
+                    const s16x2 pr = pack2<DT>(e0, e1);
+                    pf[jj][2 * v2] = pr[0];
+                    pf[jj][2 * v2 + 1] = pr[1];
+                }
+            l_run += rs0 + rs1;
         }
-        // tile 0's K buffer is the first one the loop refills: every wave must be done reading it
-        __syncthreads();
+    };
+
+    // ---- pipeline.  Iteration j: each group issues the loads of its tile j+1, works on its
+    // tile j (logits, softmax, P V), waits for its loads and meets the other waves at the
+    // barrier that publishes them.  Between barriers the waves run free, so on each SIMD the
+    // matrix work of one group's wave overlaps the vector work of the other's.
+    if (grp < nt) { load_k(0); load_v(0); }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    using std::integral_constant;
+    auto iteration = [&](auto par_c, int j) __attribute__((always_inline)) {
+        if (TSTEP * (j + 1) + grp < nt) { load_k(j + 1); load_v(j + 1); }   // into the buffers tile j-1 used
+        if (j < n_act) {
+            qk_cluster(par_c);
+            softmax_cluster(j);
+            pv_cluster(par_c);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of tile j+1 has landed
+        __builtin_amdgcn_s_barrier();
+    };
+    for (int j = 0; j < nj_loop; j += 2) {
+        iteration(integral_constant<int, 0>{}, j);
+        if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
     }
 
-    using std::integral_constant;
-    auto iteration = [&](auto par_c, int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
-        constexpr int PAR = decltype(par_c)::value;
-        if (t + 2 < nt) load_k(t + 2, PAR);
-        if (t + 1 < nt) load_v(t + 1, PAR ^ 1);
-        if (t < n_act) tile_step(par_c, t, sc, sn, mx_run);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of K(t+2), V(t+1) has landed
+    if constexpr (!WIDE) {
+        // ---- merge group 1 into group 0 through LDS (all tile buffers are idle now).  Lane-major
+        // layout: value k of wave wq's lane sits at wq*XW + k*256 + lane*4.
+        constexpr int NV = DB * 16 + 2;               // accumulator + m_ref + l_run
+        constexpr int XW = NV * 256;                  // bytes per wave
+        static_assert(4 * XW <= NSETS * GROUPB, "exchange area must fit in the tile buffers");
+        float *xch = (float *)(smem + wq * XW) + lane;
+        if (grp == 1) {
+    #pragma unroll
+            for (int db = 0; db < DB; ++db)
+    #pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(db * 16 + r) * 64] = oacc[db][r];
+            xch[(DB * 16) * 64] = m_ref;
+            xch[(DB * 16 + 1) * 64] = l_run;
+        }
         __syncthreads();
-    };
-    // iterations come in pairs so that the two logits buffers swap roles without copies; an
-    // odd tile count is rounded up (the extra iteration has no tile and only meets the barrier)
-    for (int t = 0; t < nt; t += 2) {
-        iteration(integral_constant<int, 0>{}, t, s_a, s_b);
-        iteration(integral_constant<int, 1>{}, t + 1, s_b, s_a);
+        if (grp == 1) return;
+        {
+            const float m1 = xch[(DB * 16) * 64];
+            const float l1 = xch[(DB * 16 + 1) * 64];
+            const float m = fmaxf(m_ref, m1);
+            const float a0 = __builtin_amdgcn_exp2f(m_ref - m);
+            const float a1 = __builtin_amdgcn_exp2f(m1 - m);
+            l_run = l_run * a0 + l1 * a1;
+    #pragma unroll
+            for (int db = 0; db < DB; ++db)
+    #pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] = oacc[db][r] * a0 + xch[(db * 16 + r) * 64] * a1;
+            m_ref = m;
+        }
     }
 
     // ---- epilogue: combine the two half-wave sums, normalise, store
@@ -440,36 +466,88 @@ __global__ __launch_bounds__(NW * 64, 2) void fa_fwd_kernel(const FaParams p) {
     }
 }
 
-template <int DT, int D, bool CAUSAL, int NW>
+template <int DT, int D, bool CAUSAL, bool WIDE>
 hipError_t launch(const FaParams &p, int nwork_padded, hipStream_t stream) {
-    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, NW>), dim3(nwork_padded), dim3(NW * 64), 0, stream, p);
+    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, WIDE>), dim3(nwork_padded), dim3(512), 0, stream, p);
     return hipGetLastError();
 }
 
 thread_local int g_last_hip_error = 0;
 
+
+
+// Shape checks shared by fa_fwd and fa_fwd_plan; everything here runs before any HIP call.
+int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FA_ERR_SHAPE;
+    if (D != 64 && D != 128) return FA_ERR_HEADDIM;
+    if (dtype != FA_DTYPE_F16 && dtype != FA_DTYPE_BF16) return FA_ERR_DTYPE;
+    if ((long long)B * H > 0x7fffffffLL) return FA_ERR_SHAPE;
+    if ((long long)B * H * (((long long)Nq + 127) / 128) > 0x7ffffff0LL) return FA_ERR_SHAPE;   // grid size
+    if ((long long)Nq + Nk > 0x7fffff00LL) return FA_ERR_SHAPE;                                   // int index arithmetic
+    if ((long long)Nk * D * 2 > 0x7fffffffLL) return FA_ERR_SHAPE;                                // 32-bit offsets inside one head of K/V
+    return FA_OK;
+}
+
+// FA_MODE_WIDE when there are at least as many 256-row workgroups as compute units (256), else
+// FA_MODE_SPLIT, which doubles the workgroup count and halves each one's chain of tiles; the
+// environment variable FA_FWD_MODE ("split" / "wide") overrides.
+int choose_mode(int B, int H, int Nq) {
+    const char *env = getenv("FA_FWD_MODE");
+    if (env && !strcmp(env, "split")) return FA_MODE_SPLIT;
+    if (env && !strcmp(env, "wide")) return FA_MODE_WIDE;
+    const long long wide_work = (long long)B * H * (((long long)Nq + 255) / 256);
+    return wide_work >= 256 ? FA_MODE_WIDE : FA_MODE_SPLIT;
+}
+
 }  // namespace
 
 extern "C" {
 
+int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_plan_t *plan) {
+    if (!plan) return FA_ERR_NULL;
+    const int rc = check_shape(B, H, Nq, Nk, D, dtype);
+    if (rc != FA_OK) return rc;
+    const int mode = choose_mode(B, H, Nq);
+    const int BM = mode == FA_MODE_WIDE ? 256 : 128;
+    const long long nqt = ((long long)Nq + BM - 1) / BM;
+    const long long nwork = (long long)B * H * nqt;
+    const long long tiles_k = ((long long)Nk + BN - 1) / BN;
+    long long visited = 0;
+    for (long long qt = 0; qt < nqt; ++qt) {
+        long long kmax = (long long)Nk - 1;
+        if (causal) {
+            long long last_q = qt * BM + BM - 1;
+            if (last_q > (long long)Nq - 1) last_q = (long long)Nq - 1;
+            const long long lim = last_q + ((long long)Nk - Nq);
+            if (lim < kmax) kmax = lim;
+        }
+        if (kmax >= 0) visited += kmax / BN + 1;
+    }
+    plan->mode = mode;
+    plan->block_m = BM;
+    plan->block_n = BN;
+    plan->threads = 512;
+    plan->grid = (int)(((nwork + 7) / 8) * 8);
+    plan->work_items = nwork;
+    plan->tiles_visited = visited * B * H;
+    plan->tiles_total = nwork * tiles_k;
+    plan->lds_bytes = (mode == FA_MODE_WIDE ? 1 : 2) * 4 * BN * D * 2;
+    return FA_OK;
+}
+
 int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
            int D, float scale, int causal, int dtype, void *stream) {
     if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
-    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FA_ERR_SHAPE;
-    if (D != 64 && D != 128) return FA_ERR_HEADDIM;
-    if (dtype != FA_DTYPE_F16 && dtype != FA_DTYPE_BF16) return FA_ERR_DTYPE;
+    const int rc = check_shape(B, H, Nq, Nk, D, dtype);
+    if (rc != FA_OK) return rc;
     if (!isfinite(scale)) return FA_ERR_SCALE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
     if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
 
-    const int NW = 4;
-    const int BM = 32 * NW;
-    const long long bh = (long long)B * H;
+    const int mode = choose_mode(B, H, Nq);
+    const int BM = mode == FA_MODE_WIDE ? 256 : 128;   // query rows per workgroup
     const long long nqt = ((long long)Nq + BM - 1) / BM;
-    const long long nwork = bh * nqt;
-    if (bh > 0x7fffffffLL || nwork > 0x7ffffff0LL) return FA_ERR_SHAPE;
-    // Nq + Nk must fit in int arithmetic inside the kernel
-    if ((long long)Nq + Nk > 0x7fffff00LL) return FA_ERR_SHAPE;
+    const long long nwork = (long long)B * H * nqt;
 
     FaParams p;
     p.q = (const uint16_t *)q;
@@ -485,22 +563,29 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     p.per_xcd = (int)((nwork + 7) / 8);
     const float LOG2E = 1.4426950408889634f;
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
-    p.scale_abs = fabsf(scale);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
     hipError_t e;
-    const int key = (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
+    const int key = ((mode == FA_MODE_WIDE) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
-        case 0: e = launch<0, 64, false, NW>(p, grid, st); break;
-        case 1: e = launch<0, 64, true, NW>(p, grid, st); break;
-        case 2: e = launch<0, 128, false, NW>(p, grid, st); break;
-        case 3: e = launch<0, 128, true, NW>(p, grid, st); break;
-        case 4: e = launch<1, 64, false, NW>(p, grid, st); break;
-        case 5: e = launch<1, 64, true, NW>(p, grid, st); break;
-        case 6: e = launch<1, 128, false, NW>(p, grid, st); break;
-        default: e = launch<1, 128, true, NW>(p, grid, st); break;
+        case 0: e = launch<0, 64, false, false>(p, grid, st); break;
+        case 1: e = launch<0, 64, true, false>(p, grid, st); break;
+        case 2: e = launch<0, 128, false, false>(p, grid, st); break;
+        case 3: e = launch<0, 128, true, false>(p, grid, st); break;
+        case 4: e = launch<1, 64, false, false>(p, grid, st); break;
+        case 5: e = launch<1, 64, true, false>(p, grid, st); break;
+        case 6: e = launch<1, 128, false, false>(p, grid, st); break;
+        case 7: e = launch<1, 128, true, false>(p, grid, st); break;
+        case 8: e = launch<0, 64, false, true>(p, grid, st); break;
+        case 9: e = launch<0, 64, true, true>(p, grid, st); break;
+        case 10: e = launch<0, 128, false, true>(p, grid, st); break;
+        case 11: e = launch<0, 128, true, true>(p, grid, st); break;
+        case 12: e = launch<1, 64, false, true>(p, grid, st); break;
+        case 13: e = launch<1, 64, true, true>(p, grid, st); break;
+        case 14: e = launch<1, 128, false, true>(p, grid, st); break;
+        default: e = launch<1, 128, true, true>(p, grid, st); break;
     }
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;

@@ -47,7 +47,7 @@ GOOD = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, Nq=8, 
     (dict(o=0), fa.FA_ERR_NULL), (dict(lse=0), fa.FA_ERR_NULL),
     (dict(B=0), fa.FA_ERR_SHAPE), (dict(H=-1), fa.FA_ERR_SHAPE), (dict(Nq=0), fa.FA_ERR_SHAPE),
     (dict(Nk=0), fa.FA_ERR_SHAPE), (dict(B=70000, H=70000), fa.FA_ERR_SHAPE),
-    (dict(Nq=2**31 - 1, Nk=2**31 - 1), fa.FA_ERR_SHAPE),
+    (dict(Nq=2**31 - 1, Nk=2**31 - 1), fa.FA_ERR_SHAPE), (dict(Nk=2**24, D=128), fa.FA_ERR_SHAPE),
     (dict(D=96), fa.FA_ERR_HEADDIM), (dict(D=0), fa.FA_ERR_HEADDIM), (dict(D=256), fa.FA_ERR_HEADDIM),
     (dict(dtype=2), fa.FA_ERR_DTYPE), (dict(dtype=-1), fa.FA_ERR_DTYPE),
     (dict(scale=float("nan")), fa.FA_ERR_SCALE), (dict(scale=float("inf")), fa.FA_ERR_SCALE),
@@ -67,3 +67,74 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(fa, "LIB_PATH", str(tmp_path / "libfa.so"))
     with pytest.raises(FileNotFoundError):
         fa.load()
+
+
+# ---------------------------------------------------------------- work decomposition (host logic)
+def golden():
+    import json
+    return json.load(open(os.path.join(ROOT, "tests", "golden", "paper_facts.json")))
+
+
+@pytest.mark.parametrize("mode", ["split", "wide"])
+@pytest.mark.parametrize("T", [1, 2, 8, 64, 512])
+def test_causal_plan_skips_the_tiles_above_the_diagonal(lib, monkeypatch, mode, T):
+    """Square causal problem of T query blocks: block i sees i+1 of the T key blocks, so the
+    walked fraction is (T+1)/(2T) -- the paper's "approximately 50%" for long sequences."""
+    monkeypatch.setenv("FA_FWD_MODE", mode)
+    bm = 128 if mode == "split" else 256
+    N = T * bm
+    plan = fa.fa_fwd_plan(2, 3, N, N, 128, 1, 1)
+    assert plan.mode == (fa.FA_MODE_SPLIT if mode == "split" else fa.FA_MODE_WIDE)
+    assert (plan.block_m, plan.block_n, plan.threads) == (bm, 64, 512)
+    assert plan.work_items == 6 * T and plan.grid % 8 == 0 and plan.grid >= plan.work_items
+    assert plan.tiles_total == 6 * T * (N // 64)
+    assert plan.tiles_visited * 2 * T == plan.tiles_total * (T + 1)
+    full = fa.fa_fwd_plan(2, 3, N, N, 128, 0, 1)
+    assert full.tiles_visited == full.tiles_total
+    if T >= 64:
+        fact = golden()["all_zero_blocks_saving"]
+        assert abs((1 - plan.tiles_visited / plan.tiles_total) - fact["value"]) <= fact["tolerance"]
+
+
+def test_plan_matches_brute_force_on_ragged_shapes(lib, monkeypatch):
+    import itertools
+    for mode, bm in (("split", 128), ("wide", 256)):
+        monkeypatch.setenv("FA_FWD_MODE", mode)
+        for Nq, Nk, causal in itertools.product((1, 100, 257, 640), (1, 63, 64, 65, 1000), (0, 1)):
+            plan = fa.fa_fwd_plan(1, 1, Nq, Nk, 64, causal, 0)
+            visited = 0
+            for q0 in range(0, Nq, bm):
+                rows = range(q0, min(q0 + bm, Nq))
+                tiles = set()
+                for i in rows:          # brute force over rows: which 64-key tiles hold a visible key
+                    last = min(Nk - 1, i + Nk - Nq) if causal else Nk - 1
+                    tiles.update(range(0, last // 64 + 1) if last >= 0 else ())
+                visited += len(tiles)
+            assert plan.tiles_visited == visited, (mode, Nq, Nk, causal)
+
+
+def test_mode_heuristic_and_override(lib, monkeypatch):
+    monkeypatch.delenv("FA_FWD_MODE", raising=False)
+    assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE       # 256 wide blocks: one per CU
+    assert fa.fa_fwd_plan(1, 4, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT       # 64 wide blocks: too few
+    assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(1, 32, 131072, 131072, 128, 1, 1).mode == fa.FA_MODE_WIDE
+    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).lds_bytes == 4 * 64 * 64 * 2
+    monkeypatch.setenv("FA_FWD_MODE", "split")
+    assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).lds_bytes == 2 * 4 * 64 * 128 * 2
+
+
+def test_no_mask_tensor_is_ever_needed(lib):
+    """Section 4.1 quotes 8 GB for a full 64K x 64K mask; the plan's only buffers are the LDS tiles."""
+    fact = golden()["full_mask_bytes_at_64k"]
+    assert fact["value"] == 65536 * 65536 * 2
+    assert fa.fa_fwd_plan(1, 1, 65536, 65536, 128, 1, 0).lds_bytes <= 160 * 1024
+
+
+def test_plan_rejects_bad_shapes(lib):
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_fwd_plan(1, 1, 8, 8, 96, 0, 0)
+    assert e.value.code == fa.FA_ERR_HEADDIM
+    assert fa.load().fa_fwd_plan(1, 1, 8, 8, 64, 0, 0, None) == fa.FA_ERR_NULL

@@ -26,12 +26,19 @@ SHAPES = [
 ]
 
 
+@pytest.fixture(params=["split", "wide"])
+def mode(request, monkeypatch):
+    """Force each of the two work decompositions in turn (FA_FWD_MODE of include/fa.h)."""
+    monkeypatch.setenv("FA_FWD_MODE", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_small_shapes_elementwise(oracle, shape, causal, dtype):
+def test_small_shapes_elementwise(oracle, mode, shape, causal, dtype):
     B, H, Nq, Nk, D = shape
-    print(f"case shape={shape} causal={causal} dtype={dtype}", flush=True)
+    print(f"case mode={mode} shape={shape} causal={causal} dtype={dtype}", flush=True)
     rng = np.random.default_rng(hash((shape, causal, dtype)) % (2**32))
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
     scale = 1.0 / math.sqrt(D)
@@ -41,8 +48,8 @@ def test_small_shapes_elementwise(oracle, shape, causal, dtype):
 
 
 @pytest.mark.parametrize("scale", [-0.2, 0.0, 1.0, 1e-3])
-def test_unusual_scales(oracle, scale):
-    print(f"case scale={scale}", flush=True)
+def test_unusual_scales(oracle, mode, scale):
+    print(f"case mode={mode} scale={scale}", flush=True)
     rng = np.random.default_rng(77)
     q, k, v = (rand_bits(rng, (1, 2, n, 64), I.F16) for n in (150, 210, 210))
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, I.F16)
@@ -50,8 +57,8 @@ def test_unusual_scales(oracle, scale):
     check_against_oracle(o, lse, o_ref, lse_ref, I.F16, f"scale={scale}")
 
 
-def test_rows_without_visible_keys_are_zero_with_minus_inf_lse(oracle):
-    print("case empty rows", flush=True)
+def test_rows_without_visible_keys_are_zero_with_minus_inf_lse(oracle, mode):
+    print(f"case mode={mode} empty rows", flush=True)
     rng = np.random.default_rng(78)
     q, k, v = (rand_bits(rng, (1, 2, n, 128), I.BF16) for n in (300, 100, 100))
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, 0.1, True, I.BF16)
@@ -61,9 +68,9 @@ def test_rows_without_visible_keys_are_zero_with_minus_inf_lse(oracle):
     assert (I.bits_to_f64(o, I.BF16)[:, :, :200] == 0).all()
 
 
-def test_exact_special_cases():
+def test_exact_special_cases(mode):
     """Properties that hold exactly whatever the summation order."""
-    print("case exact specials", flush=True)
+    print(f"case mode={mode} exact specials", flush=True)
     rng = np.random.default_rng(79)
     for dtype in (I.F16, I.BF16):
         q, k, v = (rand_bits(rng, (1, 2, n, 64), dtype) for n in (130, 130, 130))
@@ -77,8 +84,8 @@ def test_exact_special_cases():
         assert np.abs(I.bits_to_f64(o, dtype) - ref).max() <= 2.0 ** -7 * np.abs(ref).max()
 
 
-def test_large_logits_do_not_overflow(oracle):
-    print("case large logits", flush=True)
+def test_large_logits_do_not_overflow(oracle, mode):
+    print(f"case mode={mode} large logits", flush=True)
     rng = np.random.default_rng(80)
     q, k, v = (rand_bits(rng, (1, 1, n, 128), I.F16, m) for n, m in ((96, 6.0), (160, 6.0), (160, 1.0)))
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, 1.0, False, I.F16)   # logits ~ N(0, 36*sqrt(128))
@@ -99,9 +106,9 @@ def test_rerun_is_bitwise_reproducible():
 
 
 @pytest.mark.parametrize("name", ["C1", "C2"])
-def test_config_full(oracle, name):
+def test_config_full(oracle, mode, name):
     cfg = I.CONFIGS[name]
-    print(f"case {cfg.describe()}", flush=True)
+    print(f"case mode={mode} {cfg.describe()}", flush=True)
     q, k, v = I.make_qkv(cfg)
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
     o, lse = run_fa_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
@@ -110,8 +117,10 @@ def test_config_full(oracle, name):
 
 
 @pytest.mark.parametrize("name", ["C4", "C3", "C5"])
-def test_config_sampled_rows(oracle, name):
-    """Full-size launch; the oracle checks a seeded stratified sample of 64 rows per (b,h)."""
+def test_config_sampled_rows(oracle, monkeypatch, name):
+    """Full-size launch in the mode fa_fwd picks by itself (the one bench.py times); the oracle
+    checks a seeded stratified sample of 64 rows per (b,h)."""
+    monkeypatch.delenv("FA_FWD_MODE", raising=False)
     cfg = I.CONFIGS[name]
     print(f"case {cfg.describe()} (sampled rows)", flush=True)
     q, k, v = I.make_qkv(cfg)
