@@ -18,7 +18,12 @@ HIPCC_FLAGS = [
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
+    # per-kernel register / scratch / LDS report on stderr, checked below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+# kernel name -> {"VGPRs": n, "ScratchSize [bytes/lane]": n, ...} of the last build
+last_report: dict = {}
 
 
 def is_stale() -> bool:
@@ -26,6 +31,34 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     return any(os.path.getmtime(f) > t for f in (SRC, HDR))
+
+
+def parse_resource_report(stderr: str) -> dict:
+    """Collect the compiler's kernel-resource-usage remarks into {kernel: {field: int}}."""
+    import re
+    report, cur = {}, None
+    for line in stderr.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            cur = report.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z][A-Za-z \[\]/]*?): (\d+)", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return report
+
+
+def check_resource_report(report: dict) -> None:
+    """The kernels are written to run from registers alone: any scratch memory (a spill, or a
+    lambda the compiler left as a real call) is a performance bug of a factor of tens."""
+    if not report:
+        raise RuntimeError("no kernel-resource-usage remarks found: cannot check the build")
+    for name, r in report.items():
+        bad = {k: v for k, v in r.items() if k in ("ScratchSize [bytes/lane]", "VGPRs Spill") and v}
+        if bad:
+            raise RuntimeError(f"kernel {name} uses scratch memory: {bad}")
+        if r.get("VGPRs", 0) + r.get("AGPRs", 0) > 256:
+            raise RuntimeError(f"kernel {name} needs more than 256 registers: two waves per SIMD no longer fit")
 
 
 def build(force: bool = True, verbose: bool = False, extra=()) -> str:
@@ -38,11 +71,14 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature and says so: harmless
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed:\n{r.stdout}\n{r.stderr}")
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
+    global last_report
+    last_report = parse_resource_report(r.stderr)
+    check_resource_report(last_report)
+    if verbose:
+        for name, rep in last_report.items():
+            print(f"{name}: VGPRs {rep.get('VGPRs')} LDS {rep.get('LDS Size [bytes/block]')}", file=sys.stderr)
     return LIB
 
 

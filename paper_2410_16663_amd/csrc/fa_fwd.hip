@@ -226,44 +226,45 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // lane order, so the bank swizzle is applied on the global side: the lane that owns LDS
     // slot (row r, chunk c') fetches the global chunk that the swizzle maps there.  The NWL
     // waves that share a set of buffers load its tiles together.
-    constexpr int NI = TILEB / 1024 / NWL;        // load instructions per wave per tile
-    static_assert(TILEB % (1024 * NWL) == 0, "tile must split evenly over the waves");
+    constexpr int NINSTR = TILEB / 1024;          // load instructions per tile
+    constexpr int NI = (NINSTR + NWL - 1) / NWL;  // ... per wave, at most
     constexpr int RPI = 1024 / ROWB;              // tile rows covered by one load instruction
-    // Instruction n of this wave fills LDS bytes [(wq*NI+n)*1024, +1024) of the tile: rows
-    // row0 + n*RPI + (lane*16)/ROWB.  The V swizzle does not depend on n; the K swizzle does.
-    const int ld_row0 = wq * NI * RPI + (lane * 16) / ROWB;
+    // This wave issues instructions wq, wq + NWL, ... (< NINSTR) of a tile; instruction i fills
+    // LDS bytes [i*1024, +1024) of the tile, i.e. rows i*RPI + (lane*16)/ROWB.  Stepping i by
+    // NWL moves the row by a multiple of 16 (D = 128) or of 16 (D = 64, where the swizzle looks
+    // at row/2 mod 8), so the swizzled source chunk is the same for all of a wave's instructions.
+    static_assert((NWL * RPI) % 16 == 0, "the swizzle must not depend on the instruction index");
+    const int ld_row0 = wq * RPI + (lane * 16) / ROWB;
     const int ld_cs = ((lane * 16) % ROWB) >> 4;
-    int k_voff[NI];                               // per-lane byte offset of the K chunk, relative to the tile
-    int v_voff;                                   // same for V, relative to row n*RPI of the tile
-#pragma unroll
-    for (int n = 0; n < NI; ++n) {
-        const int r = ld_row0 + n * RPI;
-        const int ck = (D == 128) ? (ld_cs ^ (r & 15)) : (ld_cs ^ ((r >> 1) & 7));
-        k_voff[n] = ld_row0 * ROWB + ck * 16;
-    }
-    {
-        const int r = ld_row0;   // (r & 3) and ((r >> 1) & 1) are the same for every n: RPI is 4 or 8
-        const int cv = (D == 128) ? (ld_cs ^ ((r & 3) << 2)) : (ld_cs ^ (((r >> 1) & 1) << 2));
-        v_voff = ld_row0 * ROWB + cv * 16;
-    }
+    const int ck = (D == 128) ? (ld_cs ^ (ld_row0 & 15)) : (ld_cs ^ ((ld_row0 >> 1) & 7));
+    const int cv = (D == 128) ? (ld_cs ^ ((ld_row0 & 3) << 2)) : (ld_cs ^ (((ld_row0 >> 1) & 1) << 2));
+    const int k_voff = ld_row0 * ROWB + ck * 16;  // per-lane byte offset of the K chunk within the tile (first instruction)
+    const int v_voff = ld_row0 * ROWB + cv * 16;  // same for V
     unsigned char *gsm = smem + grp * GROUPB;     // this group's buffers
     const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, gsm));
-    // whole tiles take their per-lane offsets as they are (the tile start goes into the scalar
-    // base, the row step n*RPI into the instruction's immediate offset); the ragged last tile
-    // clamps its rows to the last key -- those rows are masked, they only have to be readable
+    // whole tiles take their per-lane offsets as they are (tile start and instruction step go
+    // into the scalar base); the ragged last tile clamps its rows to the last key -- those rows
+    // are masked, they only have to be readable
     auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k) __attribute__((always_inline)) {
         constexpr bool IS_K = decltype(is_k)::value;
+        const int voff = IS_K ? k_voff : v_voff;
         if (t * BN + BN <= Nk) {
-            const unsigned char *tb = uniform_ptr(gb + (size_t)t * TILEB);
-            [&]<int... Ns>(std::integer_sequence<int, Ns...>) {
-                (dma16_to_lds<Ns * 1024>(tb, (unsigned)(IS_K ? k_voff[Ns] : v_voff), lds_base + lds_off + wq * NI * 1024), ...);
-            }(std::make_integer_sequence<int, NI>{});
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int i = wq + n * NWL;
+                if (NINSTR % NWL == 0 || i < NINSTR)
+                    dma16_to_lds<0>(uniform_ptr(gb + (size_t)t * TILEB + n * NWL * 1024), (unsigned)voff,
+                                    lds_base + lds_off + i * 1024);
+            }
         } else {
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
-                const int key = min(t * BN + ld_row0 + n * RPI, Nk - 1);
-                const int src = (IS_K ? k_voff[n] : v_voff) - ld_row0 * ROWB;
-                dma16_to_lds<0>(uniform_ptr(gb), (unsigned)(key * ROWB + src), lds_base + lds_off + (wq * NI + n) * 1024);
+                const int i = wq + n * NWL;
+                if (NINSTR % NWL == 0 || i < NINSTR) {
+                    const int key = min(t * BN + ld_row0 + n * NWL * RPI, Nk - 1);
+                    dma16_to_lds<0>(uniform_ptr(gb), (unsigned)(key * ROWB + voff - ld_row0 * ROWB),
+                                    lds_base + lds_off + i * 1024);
+                }
             }
         }
     };
@@ -531,7 +532,7 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     plan->work_items = nwork;
     plan->tiles_visited = visited * B * H;
     plan->tiles_total = nwork * tiles_k;
-    plan->lds_bytes = (mode == FA_MODE_WIDE ? 1 : 2) * 4 * BN * D * 2;
+    plan->lds_bytes = (mode == FA_MODE_SPLIT ? 2 : 1) * 4 * BN * D * 2;
     return FA_OK;
 }
 
@@ -568,7 +569,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     hipStream_t st = (hipStream_t)stream;
 
     hipError_t e;
-    const int key = ((mode == FA_MODE_WIDE) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
+    const int key = (mode << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
         case 0: e = launch<0, 64, false, false>(p, grid, st); break;
         case 1: e = launch<0, 64, true, false>(p, grid, st); break;
@@ -585,7 +586,8 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
         case 12: e = launch<1, 64, false, true>(p, grid, st); break;
         case 13: e = launch<1, 64, true, true>(p, grid, st); break;
         case 14: e = launch<1, 128, false, true>(p, grid, st); break;
-        default: e = launch<1, 128, true, true>(p, grid, st); break;
+        case 15: e = launch<1, 128, true, true>(p, grid, st); break;
+        default: return FA_ERR_SHAPE;
     }
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;

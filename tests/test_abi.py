@@ -138,3 +138,14 @@ def test_plan_rejects_bad_shapes(lib):
         fa.fa_fwd_plan(1, 1, 8, 8, 96, 0, 0)
     assert e.value.code == fa.FA_ERR_HEADDIM
     assert fa.load().fa_fwd_plan(1, 1, 8, 8, 64, 0, 0, None) == fa.FA_ERR_NULL
+
+
+def test_build_report_shows_register_only_kernels():
+    """Every kernel instantiation fits two waves per SIMD and touches no scratch memory."""
+    from paper_2410_16663_amd import build
+    build.build(force=True)
+    assert len(build.last_report) == 16          # 2 dtypes x 2 head dims x causal x mode
+    for name, rep in build.last_report.items():
+        assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
+        assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name
+        assert rep["LDS Size [bytes/block]"] <= 160 * 1024, name
