@@ -129,6 +129,7 @@ def main():
         tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
     wall_ms, event_ms, _ = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
     flops = cfg.flops()
+    plan = fa.fa_fwd_plan(cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, int(cfg.causal), cfg.dtype)
     value = flops / (wall_ms * 1e-3) / 1e12
     achieved = flops / (event_ms * 1e-3) / 1e12
 
@@ -143,7 +144,8 @@ def main():
                    "note": "Q,K,V,O of this workload (64 MiB) fit in the 256 MiB Infinity Cache"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic(cfg.name),
-                     "kernel": "fa_fwd_kernel", "avg_launch_ms": round(event_ms, 5),
+                     "kernel": "fa_fwd_kernel (%s)" % ("wide" if plan.mode == fa.FA_MODE_WIDE else "split"),
+                     "avg_launch_ms": round(event_ms, 5),
                      "flops_per_launch": flops},
     }
 
@@ -151,12 +153,18 @@ def main():
         import oracle
         q, k, v = host
         nthreads = min(oracle.num_threads(), os.cpu_count() or 1)
+        passes = 0
         t0 = time.perf_counter()
-        oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
-        dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": nthreads,
+        while True:   # whole passes over the workload until about 20 core-seconds are spent
+            oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt * nthreads >= 20.0 or passes >= 8:
+                break
+        out["cpu_baseline"] = {"value": round(passes * flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": nthreads,
                                "kind": "oracle", "seconds": round(dt, 3),
-                               "sample": f"all {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name}, one pass, fp64"}
+                               "sample": f"all {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name}, "
+                                         f"{passes} full pass(es), fp64"}
 
     if not args.no_extra:
         extra = {}
