@@ -24,6 +24,7 @@ FA_DTYPE_F16 = 0
 FA_DTYPE_BF16 = 1
 FA_MODE_SPLIT = 0
 FA_MODE_WIDE = 1
+FA_MODE_WIDE_FOLD = 2
 
 # every symbol include/fa.h declares
 EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_strerror", "fa_version", "fa_last_hip_error")

@@ -64,7 +64,19 @@ struct FaParams {
     int per_xcd;    // ceil(nwork / 8)
     float c;        // |scale| * log2(e), or 1 when scale == 0
     int qmode;      // 0: use q as is, 1: negate q (scale < 0), 2: zero q (scale == 0)
+    int fold;       // wide mode, causal: deal 32-row blocks to the waves in a folded order (see fold_block)
 };
+
+// Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into
+// 32-row blocks; the blocks are taken in 8 rounds of G (= workgroups per head) consecutive
+// blocks, and workgroup g owns one block of every round -- block g of the even rounds, block
+// G-1-g of the odd ones -- so every workgroup gets the same mix of early (cheap) and late
+// (expensive) causal rows instead of 256 consecutive ones.  Wave w works on round 7-w (w < 4)
+// or w-4 (w >= 4): the two waves that share a SIMD (w and w+4) hold rounds r and 7-r.
+__host__ __device__ inline int fold_block(int G, int g, int w) {
+    const int r = w < 4 ? 7 - w : w - 4;
+    return r * G + ((r & 1) ? (G - 1 - g) : g);
+}
 
 constexpr int BN = 64;  // keys per tile
 
@@ -167,7 +179,8 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int DB = D / 32;                    // 32-row blocks of O^T
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;
-    constexpr int GROUPB = 4 * TILEB;             // one set of buffers: K0 K1 V0 V1
+    constexpr int NSTAGE = 2;                     // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead (3 measured slower)
+    constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
     constexpr int NSETS = WIDE ? 1 : 2;           // split mode: one set per group
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[NSETS * GROUPB];
@@ -190,12 +203,22 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 
     const int Nq = p.Nq, Nk = p.Nk;
     const int off = Nk - Nq;
-    const int q_wave = qt * BM + wq * 32;         // first query row of this wave
+    int q_wave = qt * BM + wq * 32;               // first query row of this wave
+    int last_row_wg = min(qt * BM + BM - 1, Nq - 1);   // last query row of the workgroup
+    if (WIDE && CAUSAL && p.fold) {
+        q_wave = fold_block(p.nqt, qt, wq) * 32;
+        last_row_wg = -1;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const int first = fold_block(p.nqt, qt, w) * 32;
+            if (first < Nq) last_row_wg = max(last_row_wg, min(first + 31, Nq - 1));
+        }
+    }
     const int qrow = q_wave + l32;                // this lane's query row
 
     int kmax_wg = Nk - 1, kmax_wave = Nk - 1;     // last key index any row may see
     if (CAUSAL) {
-        kmax_wg = min(Nk - 1, min(qt * BM + BM - 1, Nq - 1) + off);
+        kmax_wg = last_row_wg >= 0 ? min(Nk - 1, last_row_wg + off) : -1;
         kmax_wave = min(Nk - 1, min(q_wave + 31, Nq - 1) + off);
     }
     const int nt = kmax_wg >= 0 ? kmax_wg / BN + 1 : 0;     // 64-key tiles the workgroup walks
@@ -268,9 +291,9 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             }
         }
     };
-    // group tile j -> buffer j & 1
-    auto load_k = [&](int j) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, (j & 1) * TILEB, std::true_type{}); };
-    auto load_v = [&](int j) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (2 + (j & 1)) * TILEB, std::false_type{}); };
+    // group tile j lives in buffer j % NSTAGE
+    auto load_k = [&](int j, int st) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, st * TILEB, std::true_type{}); };
+    auto load_v = [&](int j, int st) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}); };
 
     // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
     auto k_frag = [&](const unsigned char *ks, int mb, int kb) __attribute__((always_inline)) -> s16x8 {
@@ -307,10 +330,10 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 #endif
     constexpr int LA = FA_LA;  // operand fragments are read this many matrix instructions ahead
 
-    // ---- S^T = K(j) Q^T for group tile j (K buffer PAR = j & 1)
-    auto qk_cluster = [&](auto par_c) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(par_c)::value;
-        const unsigned char *ks = gsm + PAR * TILEB;
+    // ---- S^T = K(j) Q^T for group tile j (K buffer ST = j % NSTAGE)
+    auto qk_cluster = [&](auto st_c) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        const unsigned char *ks = gsm + ST * TILEB;
         s16x8 fr[2 * KB];
 #pragma unroll
         for (int i = 0; i < LA; ++i) fr[i] = k_frag(ks, i & 1, i >> 1);
@@ -324,10 +347,10 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // ---- O^T += V(j)^T P(j)^T (V buffer PAR = j & 1)
-    auto pv_cluster = [&](auto par_c) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(par_c)::value;
-        const unsigned char *vs = gsm + (2 + PAR) * TILEB;
+    // ---- O^T += V(j)^T P(j)^T (V buffer ST = j % NSTAGE)
+    auto pv_cluster = [&](auto st_c) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        const unsigned char *vs = gsm + (NSTAGE + ST) * TILEB;
         s16x8 fr[4 * DB];
 #pragma unroll
         for (int i = 0; i < LA; ++i) fr[i] = v_frag(vs, i / DB, i % DB);
@@ -393,27 +416,40 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         }
     };
 
-    // ---- pipeline.  Iteration j: each group issues the loads of its tile j+1, works on its
-    // tile j (logits, softmax, P V), waits for its loads and meets the other waves at the
-    // barrier that publishes them.  Between barriers the waves run free, so on each SIMD the
-    // matrix work of one group's wave overlaps the vector work of the other's.
-    if (grp < nt) { load_k(0); load_v(0); }
+    // ---- pipeline.  Tiles are loaded PD = NSTAGE-1 iterations ahead.  Iteration j: each group
+    // issues the loads of its tile j+PD (into the buffer tile j-1 used), works on its tile j
+    // (logits, softmax, P V), waits until its share of tile j+1 has landed and meets the other
+    // waves at the barrier that publishes it.  Between barriers the waves run free, so on each
+    // SIMD the matrix work of one wave overlaps the vector work of the other.
+    constexpr int PD = NSTAGE - 1;
+    constexpr int PER_TILE = 2 * NI;              // load instructions a wave issues per tile (K and V)
+    static_assert(NINSTR % NWL == 0, "every wave must issue the same number of loads per tile");
+#pragma unroll
+    for (int j = 0; j < PD; ++j)
+        if (TSTEP * j + grp < nt) { load_k(j, j); load_v(j, j); }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     using std::integral_constant;
-    auto iteration = [&](auto par_c, int j) __attribute__((always_inline)) {
-        if (TSTEP * (j + 1) + grp < nt) { load_k(j + 1); load_v(j + 1); }   // into the buffers tile j-1 used
+    auto iteration = [&](auto st_c, int j) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;             // j % NSTAGE
+        constexpr int ST_LOAD = (ST + PD) % NSTAGE;           // (j + PD) % NSTAGE
+        const bool issued = TSTEP * (j + PD) + grp < nt;
+        if (issued) { load_k(j + PD, ST_LOAD); load_v(j + PD, ST_LOAD); }
         if (j < n_act) {
-            qk_cluster(par_c);
+            qk_cluster(st_c);
             softmax_cluster(j);
-            pv_cluster(par_c);
+            pv_cluster(st_c);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of tile j+1 has landed
+        // loads land in issue order: all but the newest (PD-1) tiles' worth must be done
+        if (issued) __builtin_amdgcn_s_waitcnt(0x0F70 | ((PD - 1) * PER_TILE));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
     };
-    for (int j = 0; j < nj_loop; j += 2) {
+    for (int j = 0; j < nj_loop; j += NSTAGE) {
         iteration(integral_constant<int, 0>{}, j);
         if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
+        if constexpr (NSTAGE == 3)
+            if (j + 2 < nj_loop) iteration(integral_constant<int, 2>{}, j + 2);
     }
 
     if constexpr (!WIDE) {
@@ -492,12 +528,44 @@ int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
 // FA_MODE_WIDE when there are at least as many 256-row workgroups as compute units (256), else
 // FA_MODE_SPLIT, which doubles the workgroup count and halves each one's chain of tiles; the
 // environment variable FA_FWD_MODE ("split" / "wide") overrides.
-int choose_mode(int B, int H, int Nq) {
+int choose_mode(int B, int H, int Nq, int causal) {
     const char *env = getenv("FA_FWD_MODE");
     if (env && !strcmp(env, "split")) return FA_MODE_SPLIT;
     if (env && !strcmp(env, "wide")) return FA_MODE_WIDE;
-    const long long wide_work = (long long)B * H * (((long long)Nq + 255) / 256);
-    return wide_work >= 256 ? FA_MODE_WIDE : FA_MODE_SPLIT;
+    if (env && !strcmp(env, "fold")) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
+    const long long nqt = ((long long)Nq + 255) / 256;
+    const long long wide_work = (long long)B * H * nqt;
+    if (wide_work < 256) return FA_MODE_SPLIT;
+    // causal, more than one block per head and about one workgroup per compute unit: nothing
+    // evens out the triangular work but the folded order.  (With more workgroups the dynamic
+    // dispatch of heavy-first work does it better: folding makes every workgroup walk nearly
+    // all tiles with ever fewer busy waves; measured 25% slower at two workgroups per CU.)
+    if (causal && nqt >= 2 && wide_work < 384 && Nq <= 4096) return FA_MODE_WIDE_FOLD;
+    return FA_MODE_WIDE;
+}
+
+// 64-key tiles the workgroup of query block qt walks (mirrors the kernel's kmax_wg)
+long long tiles_walked(int mode, long long nqt, long long qt, int Nq, int Nk, int causal) {
+    const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
+    long long kmax = (long long)Nk - 1;
+    if (causal) {
+        long long last_row = qt * BM + BM - 1;
+        if (last_row > (long long)Nq - 1) last_row = (long long)Nq - 1;
+        if (mode == FA_MODE_WIDE_FOLD) {
+            last_row = -1;
+            for (int w = 0; w < 8; ++w) {
+                const long long first = (long long)fold_block((int)nqt, (int)qt, w) * 32;
+                if (first < Nq) {
+                    const long long l = first + 31 < (long long)Nq - 1 ? first + 31 : (long long)Nq - 1;
+                    if (l > last_row) last_row = l;
+                }
+            }
+            if (last_row < 0) return 0;
+        }
+        const long long lim = last_row + ((long long)Nk - Nq);
+        if (lim < kmax) kmax = lim;
+    }
+    return kmax >= 0 ? kmax / BN + 1 : 0;
 }
 
 }  // namespace
@@ -508,22 +576,13 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     if (!plan) return FA_ERR_NULL;
     const int rc = check_shape(B, H, Nq, Nk, D, dtype);
     if (rc != FA_OK) return rc;
-    const int mode = choose_mode(B, H, Nq);
-    const int BM = mode == FA_MODE_WIDE ? 256 : 128;
+    const int mode = choose_mode(B, H, Nq, causal);
+    const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
     const long long tiles_k = ((long long)Nk + BN - 1) / BN;
     long long visited = 0;
-    for (long long qt = 0; qt < nqt; ++qt) {
-        long long kmax = (long long)Nk - 1;
-        if (causal) {
-            long long last_q = qt * BM + BM - 1;
-            if (last_q > (long long)Nq - 1) last_q = (long long)Nq - 1;
-            const long long lim = last_q + ((long long)Nk - Nq);
-            if (lim < kmax) kmax = lim;
-        }
-        if (kmax >= 0) visited += kmax / BN + 1;
-    }
+    for (long long qt = 0; qt < nqt; ++qt) visited += tiles_walked(mode, nqt, qt, Nq, Nk, causal);
     plan->mode = mode;
     plan->block_m = BM;
     plan->block_n = BN;
@@ -532,7 +591,7 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     plan->work_items = nwork;
     plan->tiles_visited = visited * B * H;
     plan->tiles_total = nwork * tiles_k;
-    plan->lds_bytes = (mode == FA_MODE_SPLIT ? 2 : 1) * 4 * BN * D * 2;
+    plan->lds_bytes = (mode == FA_MODE_SPLIT ? 2 : 1) * 4 * BN * D * 2;   // sets of 2+2 tiles
     return FA_OK;
 }
 
@@ -545,8 +604,8 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
     if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
 
-    const int mode = choose_mode(B, H, Nq);
-    const int BM = mode == FA_MODE_WIDE ? 256 : 128;   // query rows per workgroup
+    const int mode = choose_mode(B, H, Nq, causal);
+    const int BM = mode == FA_MODE_SPLIT ? 128 : 256;   // query rows per workgroup
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
 
@@ -565,11 +624,12 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     const float LOG2E = 1.4426950408889634f;
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
+    p.fold = mode == FA_MODE_WIDE_FOLD;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
     hipError_t e;
-    const int key = (mode << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
+    const int key = ((mode != FA_MODE_SPLIT) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
         case 0: e = launch<0, 64, false, false>(p, grid, st); break;
         case 1: e = launch<0, 64, true, false>(p, grid, st); break;

@@ -96,26 +96,55 @@ def test_causal_plan_skips_the_tiles_above_the_diagonal(lib, monkeypatch, mode, 
         assert abs((1 - plan.tiles_visited / plan.tiles_total) - fact["value"]) <= fact["tolerance"]
 
 
+def folded_rows(G, g, Nq):
+    """Rows of workgroup g of G under the folded assignment: one 32-row block from each of the 8
+    rounds of G consecutive blocks, in alternating direction."""
+    rows = []
+    for r in range(8):
+        blk = r * G + (G - 1 - g if r % 2 else g)
+        rows.extend(range(blk * 32, min(blk * 32 + 32, Nq)))
+    return rows
+
+
 def test_plan_matches_brute_force_on_ragged_shapes(lib, monkeypatch):
     import itertools
-    for mode, bm in (("split", 128), ("wide", 256)):
+    for mode, bm in (("split", 128), ("wide", 256), ("fold", 256)):
         monkeypatch.setenv("FA_FWD_MODE", mode)
-        for Nq, Nk, causal in itertools.product((1, 100, 257, 640), (1, 63, 64, 65, 1000), (0, 1)):
+        for Nq, Nk, causal in itertools.product((1, 100, 257, 640, 2048), (1, 63, 64, 65, 1000, 2048), (0, 1)):
             plan = fa.fa_fwd_plan(1, 1, Nq, Nk, 64, causal, 0)
-            visited = 0
-            for q0 in range(0, Nq, bm):
-                rows = range(q0, min(q0 + bm, Nq))
+            G = -(-Nq // bm)
+            visited, covered = 0, []
+            for g in range(G):
+                if mode == "fold" and causal:
+                    rows = folded_rows(G, g, Nq)
+                else:
+                    rows = list(range(g * bm, min(g * bm + bm, Nq)))
+                covered.extend(rows)
                 tiles = set()
                 for i in rows:          # brute force over rows: which 64-key tiles hold a visible key
                     last = min(Nk - 1, i + Nk - Nq) if causal else Nk - 1
                     tiles.update(range(0, last // 64 + 1) if last >= 0 else ())
-                visited += len(tiles)
+                visited += (max(tiles) + 1) if tiles else 0
+            assert sorted(covered) == list(range(Nq)), (mode, Nq)     # every row is owned exactly once
             assert plan.tiles_visited == visited, (mode, Nq, Nk, causal)
+
+
+def test_folded_assignment_balances_the_triangle(lib, monkeypatch):
+    """Square causal problem: under the folded order every workgroup sees the same number of visible pairs."""
+    Nq, G = 2048, 8
+    work = [sum(i + 1 for i in folded_rows(G, g, Nq)) for g in range(G)]
+    assert max(work) - min(work) <= 32 * 32 * 8          # within one block-diagonal of each other
+    plain = [sum(i + 1 for i in range(g * 256, g * 256 + 256)) for g in range(G)]
+    assert max(plain) > 10 * min(plain)
+    monkeypatch.setenv("FA_FWD_MODE", "fold")
+    assert fa.fa_fwd_plan(1, 32, Nq, Nq, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD
+    assert fa.fa_fwd_plan(1, 32, Nq, Nq, 128, 0, 0).mode == fa.FA_MODE_WIDE     # no triangle to balance
 
 
 def test_mode_heuristic_and_override(lib, monkeypatch):
     monkeypatch.delenv("FA_FWD_MODE", raising=False)
-    assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE       # 256 wide blocks: one per CU
+    assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD  # 256 wide blocks: one per CU
+    assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 0, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 4, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT       # 64 wide blocks: too few
     assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 32, 131072, 131072, 128, 1, 1).mode == fa.FA_MODE_WIDE

@@ -26,9 +26,9 @@ SHAPES = [
 ]
 
 
-@pytest.fixture(params=["split", "wide"])
+@pytest.fixture(params=["split", "wide", "fold"])
 def mode(request, monkeypatch):
-    """Force each of the two work decompositions in turn (FA_FWD_MODE of include/fa.h)."""
+    """Force each work decomposition in turn (FA_FWD_MODE of include/fa.h)."""
     monkeypatch.setenv("FA_FWD_MODE", request.param)
     return request.param
 
