@@ -419,8 +419,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- pipeline.  Tiles are loaded PD = NSTAGE-1 iterations ahead.  Iteration j: each group
     // issues the loads of its tile j+PD (into the buffer tile j-1 used), works on its tile j
     // (logits, softmax, P V), waits until its share of tile j+1 has landed and meets the other
-    // waves at the barrier that publishes it.  Between barriers the waves run free, so on each
-    // SIMD the matrix work of one wave overlaps the vector work of the other.
+    // waves at the barrier that publishes it.  Between barriers the waves run free.
     constexpr int PD = NSTAGE - 1;
     constexpr int PER_TILE = 2 * NI;              // load instructions a wave issues per tile (K and V)
     static_assert(NINSTR % NWL == 0, "every wave must issue the same number of loads per tile");
@@ -434,11 +433,16 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         constexpr int ST = decltype(st_c)::value;             // j % NSTAGE
         constexpr int ST_LOAD = (ST + PD) % NSTAGE;           // (j + PD) % NSTAGE
         const bool issued = TSTEP * (j + PD) + grp < nt;
-        if (issued) { load_k(j + PD, ST_LOAD); load_v(j + PD, ST_LOAD); }
         if (j < n_act) {
             qk_cluster(st_c);
+            // the loads go out between the two matrix clusters (measured 1% better than up front:
+            // their LDS writes then land mostly during the softmax, when no wave reads LDS)
+            if (issued) { load_k(j + PD, ST_LOAD); load_v(j + PD, ST_LOAD); }
             softmax_cluster(j);
             pv_cluster(st_c);
+        } else if (issued) {
+            load_k(j + PD, ST_LOAD);
+            load_v(j + PD, ST_LOAD);
         }
         // loads land in issue order: all but the newest (PD-1) tiles' worth must be done
         if (issued) __builtin_amdgcn_s_waitcnt(0x0F70 | ((PD - 1) * PER_TILE));
