@@ -314,11 +314,11 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) oacc[db] = (f32x16)(0.f);
     // Softmax state, in log2 units (logit * c).  m_ref is the reference actually subtracted
-    // before exponentiation; it follows the running maximum lazily (only when the maximum
-    // has moved by more than RESCALE_TAU), which keeps exp2 arguments <= RESCALE_TAU and
-    // spares the rescale of the accumulator on most tiles.  Any reference gives the same
-    // quotient O = acc / l.
-    constexpr float RESCALE_TAU = 8.f;
+    // before exponentiation; it follows the running maximum lazily (only when an exponential
+    // could have exceeded RESCALE_LIMIT = 2^8), which keeps P <= 256 (fine for fp16 and for the
+    // fp32 sums) and spares the rescale of the accumulator, and the row maximum itself, on
+    // almost every tile.  Any reference gives the same quotient O = acc / l.
+    constexpr float RESCALE_LIMIT = 256.f;
     float m_ref = -1e30f;
     float l_run = 0.f;         // this half-wave's share of the row sum, relative to m_ref
 
@@ -380,39 +380,74 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
                         if (key > lim) sreg[mb][r] = -INFINITY;
                     }
             }
-            // the lane's 32 logits all belong to one query
-            float mx = sreg[0][0];
+            // Exponentials against the current reference, packed as the P^T fragments: 16-key step
+            // jj takes logits registers 8*(jj%2)..+7 of block jj/2, i.e. k-slot (h, v) of step jj is
+            // key 16*jj + 8*(v/4) + 4*h + v%4.  Returns this lane's sum (its 32 logits all belong to
+            // one query).
+            auto exponentials = [&]() __attribute__((always_inline)) -> float {
+                const float nm = -m_ref;
+                float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+                for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sreg[mb][r]);
-            mx = xhalf_max(mx) * p.c;
-            // rare: move the exponent reference up and rescale what has been accumulated
-            const bool grow = mx > m_ref + RESCALE_TAU;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
-                m_ref = grow ? mx : m_ref;
-                l_run *= alpha;
+                    for (int v2 = 0; v2 < 4; ++v2) {
+                        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2], p.c, nm));
+                        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2 + 1], p.c, nm));
+                        rs0 += e0;
+                        rs1 += e1;
+                        const s16x2 pr = pack2<DT>(e0, e1);
+                        pf[jj][2 * v2] = pr[0];
+                        pf[jj][2 * v2 + 1] = pr[1];
+                    }
+                return rs0 + rs1;
+            };
+            float rs = 0.f;
+            if constexpr (D == 128) {
+                // No row maximum on the common path: the exponentials are non-negative, so a sum of
+                // at most RESCALE_LIMIT proves that none of them exceeded it.  Otherwise (the very
+                // first tile, where the sum is infinite, or a row whose maximum has risen a lot)
+                // take the row maximum, move the reference up to it, rescale what has been
+                // accumulated, and redo the exponentials -- a loop of at most two passes, so that
+                // the exponentials exist once in the code.
+#pragma nounroll
+                for (int pass = 0; pass < 2; ++pass) {
+                    rs = exponentials();
+                    const bool over = !(rs <= RESCALE_LIMIT);   // also true for inf and NaN
+                    if (pass == 1 || __builtin_amdgcn_ballot_w64(over) == 0) break;
+                    float mx = sreg[0][0];
 #pragma unroll
-                for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
-            }
-            const float nm = -m_ref;
-            float rs0 = 0.f, rs1 = 0.f;
-            // P^T fragments: 16-key step jj takes logits registers 8*(jj%2)..+7 of block jj/2,
-            // i.e. k-slot (h, v) of step jj is key 16*jj + 8*(v/4) + 4*h + v%4
+                    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
+                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sreg[mb][r]);
+                    mx = xhalf_max(mx) * p.c;
+                    const bool grow = mx > m_ref;
+                    const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
+                    m_ref = grow ? mx : m_ref;
+                    l_run *= alpha;
 #pragma unroll
-                for (int v2 = 0; v2 < 4; ++v2) {
-                    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2], p.c, nm));
-                    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sreg[jj >> 1][8 * (jj & 1) + 2 * v2 + 1], p.c, nm));
-                    rs0 += e0;
-                    rs1 += e1;
-                    const s16x2 pr = pack2<DT>(e0, e1);
-                    pf[jj][2 * v2] = pr[0];
-                    pf[jj][2 * v2 + 1] = pr[1];
+                    for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
                 }
-            l_run += rs0 + rs1;
+            } else {
+                // D = 64: keeping the logits alive for a possible second pass costs 16 registers and
+                // with them the fourth wave per SIMD, which matters more there: take the row
+                // maximum up front and move the reference when it has risen by more than 8.
+                float mx = sreg[0][0];
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sreg[mb][r]);
+                mx = xhalf_max(mx) * p.c;
+                const bool grow = mx > m_ref + 8.f;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                    const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.f;
+                    m_ref = grow ? mx : m_ref;
+                    l_run *= alpha;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+                }
+                rs = exponentials();
+            }
+            l_run += rs;
         }
     };
 

@@ -96,6 +96,37 @@ def test_large_logits_do_not_overflow(oracle, mode):
     assert (np.abs(lse - lse_ref) <= 1e-3 + 2e-7 * np.abs(lse_ref)).all()
 
 
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("pattern", ["rising", "falling", "late_spike", "staircase"])
+def test_reference_moves_with_the_row_maximum(oracle, mode, pattern, D):
+    """Logits whose row maximum keeps moving from tile to tile: the exponent reference has to
+    follow it (rescaling what was accumulated) however late and however often it jumps."""
+    print(f"case mode={mode} pattern={pattern} D={D}", flush=True)
+    rng = np.random.default_rng(81)
+    Nq, Nk = 96, 640                                   # ten 64-key tiles
+    qf = rng.standard_normal((1, 2, Nq, D), dtype=np.float32)
+    kf = rng.standard_normal((1, 2, Nk, D), dtype=np.float32) * np.float32(0.05)
+    vf = rng.standard_normal((1, 2, Nk, D), dtype=np.float32)
+    # keys get a component along each head's mean query direction, so q.k has a large common part
+    u = qf.mean(axis=2, keepdims=True)
+    u /= np.linalg.norm(u, axis=-1, keepdims=True)
+    qf = qf * np.float32(0.2) + 6.0 * u                 # q.u ~ 6 for every row
+    j = np.arange(Nk, dtype=np.float32)
+    amp = {"rising": j / 16.0,                          # +4 per tile in q.k/6 ... steadily upward
+           "falling": (Nk - j) / 16.0,
+           "late_spike": np.where(j == Nk - 3, 30.0, 0.0),
+           "staircase": np.floor(j / 64.0) * 6.0}[pattern].astype(np.float32)
+    kf = kf + amp[None, None, :, None] * u
+    q, k, v = (I.f32_to_bits(a, I.F16) for a in (qf, kf, vf))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, 1.0, False, I.F16)
+    o, lse = run_fa_fwd(q, k, v, 1.0, False, I.F16)
+    of = I.bits_to_f64(o, I.F16)
+    assert np.isfinite(of).all() and np.isfinite(lse).all()
+    assert np.abs(of - o_ref).max() <= 1e-2
+    # lse values reach the hundreds here: fp32 output and fp32 accumulation of a 128-term dot product
+    assert (np.abs(lse - lse_ref) <= 1e-3 + 1e-6 * np.abs(lse_ref)).all()
+
+
 def test_rerun_is_bitwise_reproducible():
     print("case reproducible", flush=True)
     cfg = I.CONFIGS["C1"]
