@@ -268,10 +268,10 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // whole tiles take their per-lane offsets as they are (tile start and instruction step go
     // into the scalar base); the ragged last tile clamps its rows to the last key -- those rows
     // are masked, they only have to be readable
-    auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k) __attribute__((always_inline)) {
+    auto load_tile = [&](const unsigned char *gb, int t, int lds_off, auto is_k, auto full_c) __attribute__((always_inline)) {
         constexpr bool IS_K = decltype(is_k)::value;
         const int voff = IS_K ? k_voff : v_voff;
-        if (t * BN + BN <= Nk) {
+        if (decltype(full_c)::value || t * BN + BN <= Nk) {
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
                 const int i = wq + n * NWL;
@@ -292,8 +292,9 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         }
     };
     // group tile j lives in buffer j % NSTAGE
-    auto load_k = [&](int j, int st) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, st * TILEB, std::true_type{}); };
-    auto load_v = [&](int j, int st) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}); };
+    // full_c: the caller knows the tile lies wholly inside K/V (no check, no clamped path)
+    auto load_k = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, st * TILEB, std::true_type{}, full_c); };
+    auto load_v = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}, full_c); };
 
     // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
     auto k_frag = [&](const unsigned char *ks, int mb, int kb) __attribute__((always_inline)) -> s16x8 {
@@ -364,11 +365,12 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     };
 
     // ---- softmax of group tile j: logits in sreg -> packed exponentials in pf, running sums
-    auto softmax_cluster = [&](int j) __attribute__((always_inline)) {
+    auto softmax_cluster = [&](int j, auto maybe_masked_c) __attribute__((always_inline)) {
         {
             const int k0 = (TSTEP * j + grp) * BN;
             // mask only when the tile straddles the diagonal or the end of K
-            const bool need_mask = (k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off));
+            const bool need_mask = decltype(maybe_masked_c)::value &&
+                                   ((k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off)));
             if (need_mask) {
                 int lim = Nk - 1;
                 if (CAUSAL) lim = min(lim, qrow + off);
@@ -460,10 +462,11 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     static_assert(NINSTR % NWL == 0, "every wave must issue the same number of loads per tile");
 #pragma unroll
     for (int j = 0; j < PD; ++j)
-        if (TSTEP * j + grp < nt) { load_k(j, j); load_v(j, j); }
+        if (TSTEP * j + grp < nt) { load_k(j, j, std::false_type{}); load_v(j, j, std::false_type{}); }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     using std::integral_constant;
+    // general iteration: every condition checked
     auto iteration = [&](auto st_c, int j) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;             // j % NSTAGE
         constexpr int ST_LOAD = (ST + PD) % NSTAGE;           // (j + PD) % NSTAGE
@@ -472,23 +475,53 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             qk_cluster(st_c);
             // the loads go out between the two matrix clusters (measured 1% better than up front:
             // their LDS writes then land mostly during the softmax, when no wave reads LDS)
-            if (issued) { load_k(j + PD, ST_LOAD); load_v(j + PD, ST_LOAD); }
-            softmax_cluster(j);
+            if (issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
+            softmax_cluster(j, std::true_type{});
             pv_cluster(st_c);
         } else if (issued) {
-            load_k(j + PD, ST_LOAD);
-            load_v(j + PD, ST_LOAD);
+            load_k(j + PD, ST_LOAD, std::false_type{});
+            load_v(j + PD, ST_LOAD, std::false_type{});
         }
         // loads land in issue order: all but the newest (PD-1) tiles' worth must be done
         if (issued) __builtin_amdgcn_s_waitcnt(0x0F70 | ((PD - 1) * PER_TILE));
         else __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
     };
-    for (int j = 0; j < nj_loop; j += NSTAGE) {
+    // interior iteration: this wave's tile j is active and needs no mask, and tile j+1 of its group
+    // exists and lies wholly inside K/V -- straight-line code, no checks
+    static_assert(NSTAGE == 2, "the interior loop is written for two buffers");
+    auto interior = [&](auto st_c, int j) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        qk_cluster(st_c);
+        load_k(j + 1, ST ^ 1, std::true_type{});
+        load_v(j + 1, ST ^ 1, std::true_type{});
+        softmax_cluster(j, std::false_type{});
+        pv_cluster(st_c);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+    };
+    // number of leading iterations that are interior for this wave (every wave runs nj_loop
+    // iterations and meets nj_loop barriers, whichever of the two loops each one is in)
+    int j_int = 0;
+    {
+        // tile TSTEP*j+grp is unmasked for this wave while its last key is <= the first row's limit
+        const int last_free_key = CAUSAL ? min(Nk - 1, q_wave + off) : Nk - 1;       // may be negative
+        const int unmasked = last_free_key >= BN - 1 ? ((last_free_key - (BN - 1)) / BN - grp) / TSTEP + 1 : 0;
+        const int full_tiles = Nk / BN;                                              // tiles wholly inside K/V
+        const int next_full = (full_tiles - 1 - grp) / TSTEP;                        // j with tile j+1 full: j < next_full
+        const int ntg = nt > grp ? (nt - 1 - grp) / TSTEP + 1 : 0;                   // tiles of this wave's group
+        j_int = min(min(unmasked, n_act), min(next_full, ntg - 1));
+        if (last_free_key < BN - 1 + grp * BN || full_tiles - 1 - grp < 0) j_int = 0;
+        j_int = max(j_int, 0) & ~1;                                                  // whole pairs
+    }
+    int j = 0;
+    for (; j < j_int; j += 2) {
+        interior(integral_constant<int, 0>{}, j);
+        interior(integral_constant<int, 1>{}, j + 1);
+    }
+    for (; j < nj_loop; j += 2) {
         iteration(integral_constant<int, 0>{}, j);
         if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
-        if constexpr (NSTAGE == 3)
-            if (j + 2 < nj_loop) iteration(integral_constant<int, 2>{}, j + 2);
     }
 
     if constexpr (!WIDE) {
