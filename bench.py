@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak
 METRIC = "attention fwd TFLOP/s and % of MFMA fp16/bf16 peak (1 MI355X)"
 
 
@@ -74,6 +75,35 @@ def time_config(cfg, tensors, steps, warmup, torch, fa):
     return wall_ms, event_ms, (to, tl)
 
 
+def time_decode(cfg, tensors, steps, warmup, torch, fa):
+    """The decoding workload through fa_fwd_splitkv (workspace allocated once, outside the timed region).
+    Returns the HIP-event mean ms per call (two kernels: partial attention + merge) and the plan."""
+    tq, tk, tv = tensors
+    dev = tq.device
+    to = torch.empty((cfg.B, cfg.H, cfg.Nq, cfg.D), dtype=torch.int16, device=dev)
+    tl = torch.empty((cfg.B, cfg.H, cfg.Nq), dtype=torch.float32, device=dev)
+    plan = fa.fa_fwd_splitkv_plan(cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, int(cfg.causal), cfg.dtype, 0)
+    ws = torch.empty((plan.workspace_bytes + 3) // 4, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+
+    def launch():
+        fa.fa_fwd_splitkv(tq, tk, tv, to, tl, cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, cfg.scale, int(cfg.causal),
+                          cfg.dtype, 0, ws, plan.workspace_bytes, sp)
+
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        launch()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps, plan
+
+
 def read_traffic(workload):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
     path = os.path.join(ROOT, "profiles", f"fa_fwd_{workload}_hbm_traffic.txt")
@@ -86,12 +116,31 @@ def read_traffic(workload):
     return None
 
 
+def decode_entry(I, torch, fa, steps, warmup):
+    """Appendix C's decoding shape through the split-KV entry point, priced against HBM: the algorithmic
+    bytes of a call are K and V read once (Q, O, lse and the partial results are thousands of times smaller)."""
+    c = I.DECODE
+    tensors = device_inputs_on_gpu(c, torch)
+    ms, plan = time_decode(c, tensors, steps, warmup, torch, fa)
+    kv_bytes = 2.0 * c.B * c.H * c.Nk * c.D * 2
+    gbs = kv_bytes / (ms * 1e-3) / 1e9
+    return {"workload": c.describe(), "entry_point": "fa_fwd_splitkv", "nsplit": plan.nsplit,
+            "grid": [plan.grid_x, plan.grid_y], "ms_per_call": round(ms, 5), "steps": steps,
+            "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic("splitkv_DEC"),
+                         "kernel": "fa_fwd_kernel (wide, split-KV) + fa_combine_kernel",
+                         "bytes_per_call": kv_bytes}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--gpu-inputs", action="store_true",
@@ -122,6 +171,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.decode_only:
+        print(json.dumps({"decode": decode_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
+        return
     if args.gpu_inputs:
         args.no_cpu = True
         tensors, host = device_inputs_on_gpu(cfg, torch), None
@@ -181,6 +233,9 @@ def main():
             extra[name] = {"workload": c.describe(), "ms_per_launch": round(e_ms, 4), "tflops": round(tf, 2),
                            "pct_of_mfma_peak": round(100.0 * tf / MFMA_PEAK_TFLOPS, 2), "steps": steps,
                            "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)"}
+        del tensors
+        torch.cuda.empty_cache()
+        extra["DEC"] = decode_entry(I, torch, fa, 50, 5)
         out["other_workloads"] = extra
 
     print(json.dumps(out), flush=True)

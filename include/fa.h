@@ -25,6 +25,8 @@ extern "C" {
 #define FA_ERR_SCALE    -5 /* scale is NaN or infinite */
 #define FA_ERR_ALIGN    -6 /* q, k, v or o not 16-byte aligned, or lse not 4-byte aligned */
 #define FA_ERR_LAUNCH   -7 /* the HIP runtime rejected the launch (see fa_last_hip_error) */
+#define FA_ERR_WORKSPACE -8 /* fa_fwd_splitkv: workspace NULL or smaller than fa_fwd_splitkv_plan reports */
+#define FA_ERR_NSPLIT   -9 /* fa_fwd_splitkv: nsplit > 1024 */
 
 #define FA_DTYPE_F16  0 /* IEEE binary16 */
 #define FA_DTYPE_BF16 1 /* bfloat16 */
@@ -96,6 +98,47 @@ typedef struct fa_plan {
  * without touching the GPU.  Same shape checks and error codes as fa_fwd.
  */
 int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_plan_t *plan);
+
+/*
+ * fa_fwd_splitkv -- the same operation as fa_fwd (same formula, same arguments, same
+ * results up to fp32 rounding order) for the decoding shape of appendix C: one or a few
+ * query rows per head against a long K/V cache, where B * H * ceil(Nq/256) workgroups cannot
+ * fill the chip.  The key tiles of every 256-row query block are cut into `nsplit` runs, one
+ * workgroup each; every run leaves an unnormalised partial result (accumulator, exponent
+ * reference, row sum -- the running quantities of appendix A) in `workspace`, and a second
+ * kernel merges them: lse = logsumexp over runs, o = sum_runs exp(lse_run - lse) o_run.
+ * Bound by reading K and V once from HBM.
+ *
+ *   nsplit          : > 0: number of runs (clamped to the number of 64-key tiles, at most 1024);
+ *                     <= 0: the library picks (256 workgroups at D = 128, 512 at D = 64, runs of >= 4 tiles)
+ *   workspace       : DEVICE pointer, 16-byte aligned, caller-owned scratch of at least
+ *                     fa_fwd_splitkv_plan(...).workspace_bytes; contents on entry are ignored,
+ *                     contents on return are unspecified; must not alias any other argument
+ *   workspace_bytes : size of `workspace`
+ *   everything else : as for fa_fwd
+ *
+ * Enqueues two kernels on `stream`, allocates nothing, does not synchronise.  Calls that share
+ * a workspace must be ordered (same stream).  Returns FA_OK or a negative FA_ERR_* code; on an
+ * argument error nothing is launched.
+ */
+int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse,
+                   int B, int H, int Nq, int Nk, int D, float scale, int causal, int dtype,
+                   int nsplit, void *workspace, long long workspace_bytes, void *stream);
+
+typedef struct fa_splitkv_plan {
+    int nsplit;                 /* runs actually used */
+    int grid_x, grid_y;         /* first kernel: work items (rounded up to a multiple of 8) x runs */
+    int combine_grid;           /* second kernel: blocks of 256 threads */
+    long long work_items;       /* B * H * ceil(Nq / 256) */
+    long long workspace_bytes;  /* nsplit * B * H * Nq * (D + 2) * 4 */
+} fa_splitkv_plan_t;
+
+/*
+ * fa_fwd_splitkv_plan -- host-only: the launch shape and workspace size fa_fwd_splitkv uses for
+ * the given problem and `nsplit` argument.  *plan is a caller-owned HOST pointer.
+ */
+int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, int nsplit,
+                        fa_splitkv_plan_t *plan);
 
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);

@@ -20,6 +20,8 @@ FA_ERR_DTYPE = -4
 FA_ERR_SCALE = -5
 FA_ERR_ALIGN = -6
 FA_ERR_LAUNCH = -7
+FA_ERR_WORKSPACE = -8
+FA_ERR_NSPLIT = -9
 FA_DTYPE_F16 = 0
 FA_DTYPE_BF16 = 1
 FA_MODE_SPLIT = 0
@@ -27,7 +29,8 @@ FA_MODE_WIDE = 1
 FA_MODE_WIDE_FOLD = 2
 
 # every symbol include/fa.h declares
-EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_strerror", "fa_version", "fa_last_hip_error")
+EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_strerror", "fa_version",
+           "fa_last_hip_error")
 
 _lib = None
 
@@ -38,6 +41,13 @@ class FaPlan(ctypes.Structure):
                 ("threads", ctypes.c_int), ("grid", ctypes.c_int), ("lds_bytes", ctypes.c_int),
                 ("work_items", ctypes.c_longlong), ("tiles_visited", ctypes.c_longlong),
                 ("tiles_total", ctypes.c_longlong)]
+
+
+class FaSplitKvPlan(ctypes.Structure):
+    """fa_splitkv_plan_t of include/fa.h."""
+    _fields_ = [("nsplit", ctypes.c_int), ("grid_x", ctypes.c_int), ("grid_y", ctypes.c_int),
+                ("combine_grid", ctypes.c_int), ("work_items", ctypes.c_longlong),
+                ("workspace_bytes", ctypes.c_longlong)]
 
 
 class FaError(RuntimeError):
@@ -61,6 +71,11 @@ def load() -> ctypes.CDLL:
             ctypes.c_float, ctypes.c_int, ctypes.c_int, vp]
         lib.fa_fwd_plan.restype = ctypes.c_int
         lib.fa_fwd_plan.argtypes = [ctypes.c_int] * 7 + [ctypes.POINTER(FaPlan)]
+        lib.fa_fwd_splitkv.restype = ctypes.c_int
+        lib.fa_fwd_splitkv.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
+            ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_longlong, vp]
+        lib.fa_fwd_splitkv_plan.restype = ctypes.c_int
+        lib.fa_fwd_splitkv_plan.argtypes = [ctypes.c_int] * 8 + [ctypes.POINTER(FaSplitKvPlan)]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -98,6 +113,33 @@ def fa_fwd_plan(B, H, Nq, Nk, D, causal, dtype) -> FaPlan:
     """fa_fwd_plan of include/fa.h (host only, no GPU needed); raises FaError on a bad shape."""
     plan = FaPlan()
     rc = load().fa_fwd_plan(int(B), int(H), int(Nq), int(Nk), int(D), int(causal), int(dtype), ctypes.byref(plan))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return plan
+
+
+def fa_fwd_splitkv_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, workspace, workspace_bytes,
+                       stream=0) -> int:
+    """Call fa_fwd_splitkv and return its status code unchanged."""
+    return load().fa_fwd_splitkv(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nq),
+                                 int(Nk), int(D), float(scale), int(causal), int(dtype), int(nsplit),
+                                 _addr(workspace), int(workspace_bytes), _addr(stream))
+
+
+def fa_fwd_splitkv(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, workspace, workspace_bytes,
+                   stream=0) -> None:
+    """fa_fwd_splitkv of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_fwd_splitkv_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, workspace,
+                            workspace_bytes, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, dtype, nsplit=0) -> FaSplitKvPlan:
+    """fa_fwd_splitkv_plan of include/fa.h (host only); raises FaError on a bad shape or nsplit."""
+    plan = FaSplitKvPlan()
+    rc = load().fa_fwd_splitkv_plan(int(B), int(H), int(Nq), int(Nk), int(D), int(causal), int(dtype), int(nsplit),
+                                    ctypes.byref(plan))
     if rc != FA_OK:
         raise FaError(rc)
     return plan

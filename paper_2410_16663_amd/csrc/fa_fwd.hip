@@ -65,6 +65,12 @@ struct FaParams {
     float c;        // |scale| * log2(e), or 1 when scale == 0
     int qmode;      // 0: use q as is, 1: negate q (scale < 0), 2: zero q (scale == 0)
     int fold;       // wide mode, causal: deal 32-row blocks to the waves in a folded order (see fold_block)
+    // split-KV only: the keys of every query block are cut into nsplit runs of tiles, one
+    // workgroup each (blockIdx.y); a workgroup leaves its unnormalised accumulator, exponent
+    // reference and row sum here for the combine kernel
+    int nsplit;
+    float *part_o;  // [nsplit][B*H*Nq][D]
+    float *part_ml; // [nsplit][B*H*Nq][2]: reference (log2 units), row sum relative to it
 };
 
 // Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into
@@ -170,8 +176,13 @@ __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, u
 // WIDE = true: the eight waves work on 256 different query rows and all walk the same key
 //   tiles, loaded once for the whole workgroup.  Halves the K/V traffic into LDS per unit of
 //   work: the shape for long sequences.
-template <int DT, int D, bool CAUSAL, bool WIDE>
+// SPLITKV = true (wide only): blockIdx.y picks one of p.nsplit runs of the workgroup's key tiles;
+//   the result is left unnormalised in p.part_o / p.part_ml for fa_combine_kernel.  The shape for
+//   few queries against a long K/V (decoding, chunked prefill), where batch x heads x query
+//   blocks alone cannot fill the chip.
+template <int DT, int D, bool CAUSAL, bool WIDE, bool SPLITKV = false>
 __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
+    static_assert(WIDE || !SPLITKV, "split-KV is built on the wide decomposition");
     constexpr int NWL = WIDE ? 8 : 4;             // waves that load one tile together
     constexpr int BM = WIDE ? 256 : 128;          // query rows per workgroup
     constexpr int TSTEP = WIDE ? 1 : 2;           // a group's consecutive tiles are TSTEP apart
@@ -179,7 +190,12 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int DB = D / 32;                    // 32-row blocks of O^T
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;
-    constexpr int NSTAGE = 2;                     // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead (3 measured slower)
+#ifndef FA_SPLITKV_STAGES
+#define FA_SPLITKV_STAGES 3
+#endif
+    // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead.  Two for the compute-bound shapes (3 measured
+    // slower); the split-KV shapes are bound by HBM latency x bandwidth and take a third
+    constexpr int NSTAGE = SPLITKV ? FA_SPLITKV_STAGES : 2;
     constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
     constexpr int NSETS = WIDE ? 1 : 2;           // split mode: one set per group
 
@@ -221,11 +237,18 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         kmax_wg = last_row_wg >= 0 ? min(Nk - 1, last_row_wg + off) : -1;
         kmax_wave = min(Nk - 1, min(q_wave + 31, Nq - 1) + off);
     }
-    const int nt = kmax_wg >= 0 ? kmax_wg / BN + 1 : 0;     // 64-key tiles the workgroup walks
-    // group-local tile j is global tile TSTEP*j + grp
+    const int nt_all = kmax_wg >= 0 ? kmax_wg / BN + 1 : 0; // 64-key tiles the query block needs
+    // this workgroup walks tiles t_lo .. t_lo + nt - 1 of them (all of them unless split-KV)
+    int t_lo = 0, nt = nt_all;
+    if constexpr (SPLITKV) {
+        t_lo = (int)((long long)blockIdx.y * nt_all / p.nsplit);
+        nt = (int)((long long)(blockIdx.y + 1) * nt_all / p.nsplit) - t_lo;
+    }
+    // group-local tile j is global tile t_lo + TSTEP*j + grp
     const int nj_loop = (nt + TSTEP - 1) / TSTEP;            // tiles of group 0 (>= those of group 1)
     int n_act = 0;                                           // group tiles this wave works on
     if (q_wave < Nq && kmax_wave >= 0 && kmax_wave / BN >= grp) n_act = (kmax_wave / BN - grp) / TSTEP + 1;
+    if constexpr (SPLITKV) n_act = max(n_act - t_lo, 0);
 
     const size_t kv_head = (size_t)bh * Nk * D;
     const unsigned char *kgb = (const unsigned char *)(p.k + kv_head);
@@ -293,8 +316,8 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     };
     // group tile j lives in buffer j % NSTAGE
     // full_c: the caller knows the tile lies wholly inside K/V (no check, no clamped path)
-    auto load_k = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(kgb, TSTEP * j + grp, st * TILEB, std::true_type{}, full_c); };
-    auto load_v = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(vgb, TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}, full_c); };
+    auto load_k = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(kgb, t_lo + TSTEP * j + grp, st * TILEB, std::true_type{}, full_c); };
+    auto load_v = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(vgb, t_lo + TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}, full_c); };
 
     // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
     auto k_frag = [&](const unsigned char *ks, int mb, int kb) __attribute__((always_inline)) -> s16x8 {
@@ -367,7 +390,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- softmax of group tile j: logits in sreg -> packed exponentials in pf, running sums
     auto softmax_cluster = [&](int j, auto maybe_masked_c) __attribute__((always_inline)) {
         {
-            const int k0 = (TSTEP * j + grp) * BN;
+            const int k0 = (t_lo + TSTEP * j + grp) * BN;
             // mask only when the tile straddles the diagonal or the end of K
             const bool need_mask = decltype(maybe_masked_c)::value &&
                                    ((k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off)));
@@ -472,10 +495,12 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         constexpr int ST_LOAD = (ST + PD) % NSTAGE;           // (j + PD) % NSTAGE
         const bool issued = TSTEP * (j + PD) + grp < nt;
         if (j < n_act) {
-            qk_cluster(st_c);
             // the loads go out between the two matrix clusters (measured 1% better than up front:
-            // their LDS writes then land mostly during the softmax, when no wave reads LDS)
-            if (issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
+            // their LDS writes then land mostly during the softmax, when no wave reads LDS);
+            // split-KV waits on HBM, not on LDS: there they go out first
+            if (SPLITKV && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
+            qk_cluster(st_c);
+            if (!SPLITKV && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
             softmax_cluster(j, std::true_type{});
             pv_cluster(st_c);
         } else if (issued) {
@@ -489,7 +514,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     };
     // interior iteration: this wave's tile j is active and needs no mask, and tile j+1 of its group
     // exists and lies wholly inside K/V -- straight-line code, no checks
-    static_assert(NSTAGE == 2, "the interior loop is written for two buffers");
+    // (written for two buffers; with more the general loop does everything)
     auto interior = [&](auto st_c, int j) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;
         qk_cluster(st_c);
@@ -512,16 +537,27 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         const int ntg = nt > grp ? (nt - 1 - grp) / TSTEP + 1 : 0;                   // tiles of this wave's group
         j_int = min(min(unmasked, n_act), min(next_full, ntg - 1));
         if (last_free_key < BN - 1 + grp * BN || full_tiles - 1 - grp < 0) j_int = 0;
+        if constexpr (SPLITKV)   // the same three limits, counted from this workgroup's first tile
+            j_int = last_free_key >= BN - 1 ? min(min(unmasked - t_lo, n_act), min(full_tiles - 1 - t_lo, nt - 1)) : 0;
         j_int = max(j_int, 0) & ~1;                                                  // whole pairs
     }
     int j = 0;
-    for (; j < j_int; j += 2) {
-        interior(integral_constant<int, 0>{}, j);
-        interior(integral_constant<int, 1>{}, j + 1);
-    }
-    for (; j < nj_loop; j += 2) {
-        iteration(integral_constant<int, 0>{}, j);
-        if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
+    if constexpr (NSTAGE == 2) {
+        for (; j < j_int; j += 2) {
+            interior(integral_constant<int, 0>{}, j);
+            interior(integral_constant<int, 1>{}, j + 1);
+        }
+        for (; j < nj_loop; j += 2) {
+            iteration(integral_constant<int, 0>{}, j);
+            if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
+        }
+    } else {
+        static_assert(NSTAGE == 3, "two or three buffers");
+        for (; j < nj_loop; j += 3) {
+            iteration(integral_constant<int, 0>{}, j);
+            if (j + 1 < nj_loop) iteration(integral_constant<int, 1>{}, j + 1);
+            if (j + 2 < nj_loop) iteration(integral_constant<int, 2>{}, j + 2);
+        }
     }
 
     if constexpr (!WIDE) {
@@ -558,6 +594,24 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 
     // ---- epilogue: combine the two half-wave sums, normalise, store
     const float l_tot = xhalf_sum(l_run);
+    if constexpr (SPLITKV) {
+        if (qrow < Nq) {
+            const size_t row = (size_t)blockIdx.y * ((size_t)p.nwork / p.nqt) * Nq + (size_t)bh * Nq + qrow;
+            float *po = p.part_o + row * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 x = {oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
+                    *(float4 *)(po + db * 32 + 8 * g) = x;
+                }
+            if (h == 0) {
+                const float2 ml = {m_ref, l_tot};
+                *(float2 *)(p.part_ml + row * 2) = ml;
+            }
+        }
+        return;
+    }
     if (qrow < Nq) {
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         uint16_t *op = p.o + ((size_t)bh * Nq + qrow) * D + 4 * h;
@@ -575,9 +629,55 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     }
 }
 
+// Merge of the split-KV partial results (the same merge the split mode does between its two
+// wave groups): with M = max_s m_s, L = sum_s l_s 2^(m_s - M), the row is
+// o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
+// left m = -1e30, l = 0, acc = 0 and drops out; a row with no visible key at all gets o = 0,
+// lse = -inf.  One thread per (row, 4 consecutive d).
+template <int DT, int D>
+__global__ __launch_bounds__(256) void fa_combine_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                                         uint16_t *__restrict__ o, float *__restrict__ lse, long long rows,
+                                                         int nsplit) {
+    constexpr int TPR = D / 4;                    // threads per row
+    const long long row = (long long)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    const int d4 = threadIdx.x % TPR;
+    if (row >= rows) return;
+    float M = -1e30f;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[((size_t)s * rows + row) * 2]);
+    float L = 0.f;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < nsplit; ++s) {
+        const float2 ml = *(const float2 *)(part_ml + ((size_t)s * rows + row) * 2);
+        const float w = __builtin_amdgcn_exp2f(ml.x - M);
+        const float4 x = *(const float4 *)(part_o + ((size_t)s * rows + row) * D + 4 * d4);
+        L += ml.y * w;
+        acc.x += x.x * w;
+        acc.y += x.y * w;
+        acc.z += x.z * w;
+        acc.w += x.w * w;
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const s16x2 a = pack2<DT>(acc.x * inv, acc.y * inv);
+    const s16x2 b = pack2<DT>(acc.z * inv, acc.w * inv);
+    const s16x4 st = {a[0], a[1], b[0], b[1]};
+    *(s16x4 *)(o + (size_t)row * D + 4 * d4) = st;
+    if (d4 == 0) lse[row] = L > 0.f ? (M + __log2f(L)) * 0.6931471805599453f : -INFINITY;
+}
+
 template <int DT, int D, bool CAUSAL, bool WIDE>
 hipError_t launch(const FaParams &p, int nwork_padded, hipStream_t stream) {
     hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, WIDE>), dim3(nwork_padded), dim3(512), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int DT, int D, bool CAUSAL>
+hipError_t launch_splitkv(const FaParams &p, int nwork_padded, long long rows, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, true, true>), dim3(nwork_padded, p.nsplit), dim3(512), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int RPB = 256 / (D / 4);            // rows per combine block
+    hipLaunchKernelGGL((fa_combine_kernel<DT, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream,
+                       p.part_o, p.part_ml, p.o, p.lse, rows, p.nsplit);
     return hipGetLastError();
 }
 
@@ -640,6 +740,25 @@ long long tiles_walked(int mode, long long nqt, long long qt, int Nq, int Nk, in
     return kmax >= 0 ? kmax / BN + 1 : 0;
 }
 
+// Split-KV launch shape.  nsplit_in > 0 is taken as given (clamped to the number of key
+// tiles); otherwise pick enough runs for one workgroup per compute unit at D = 128 and two at
+// D = 64, whose tiles are half the bytes (measured best: the path is bound by HBM, which that
+// many workgroups' loads in flight saturate, and every further run only adds its fixed cost
+// and its share of the merge), each run at least four tiles long.
+constexpr int SPLITKV_MAX = 1024;
+int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
+    long long n = nsplit_in;
+    if (n <= 0) {
+        const long long target = D == 128 ? 256 : 512;
+        n = (target + nwork - 1) / nwork;
+        if (n > tiles_k / 4) n = tiles_k / 4;
+    }
+    if (n > tiles_k) n = tiles_k;
+    if (n > SPLITKV_MAX) n = SPLITKV_MAX;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
 }  // namespace
 
 extern "C" {
@@ -697,6 +816,9 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
     p.fold = mode == FA_MODE_WIDE_FOLD;
+    p.nsplit = 1;
+    p.part_o = nullptr;
+    p.part_ml = nullptr;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
@@ -728,6 +850,83 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     return FA_OK;
 }
 
+int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, int nsplit,
+                        fa_splitkv_plan_t *plan) {
+    (void)causal;
+    if (!plan) return FA_ERR_NULL;
+    const int rc = check_shape(B, H, Nq, Nk, D, dtype);
+    if (rc != FA_OK) return rc;
+    if (nsplit > SPLITKV_MAX) return FA_ERR_NSPLIT;
+    const long long nqt = ((long long)Nq + 255) / 256;
+    const long long nwork = (long long)B * H * nqt;
+    const long long tiles_k = ((long long)Nk + BN - 1) / BN;
+    const int ns = choose_nsplit(nwork, tiles_k, D, nsplit);
+    const long long rows = (long long)B * H * Nq;
+    plan->nsplit = ns;
+    plan->grid_x = (int)(((nwork + 7) / 8) * 8);
+    plan->grid_y = ns;
+    plan->combine_grid = (int)((rows + (1024 / D) - 1) / (1024 / D));
+    plan->work_items = nwork;
+    plan->workspace_bytes = (long long)ns * rows * (D + 2) * 4;
+    return FA_OK;
+}
+
+int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
+                   int D, float scale, int causal, int dtype, int nsplit, void *workspace, long long workspace_bytes,
+                   void *stream) {
+    if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
+    fa_splitkv_plan_t pl;
+    const int rc = fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, dtype, nsplit, &pl);
+    if (rc != FA_OK) return rc;
+    if (!isfinite(scale)) return FA_ERR_SCALE;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
+    if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < pl.workspace_bytes) return FA_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15) return FA_ERR_ALIGN;
+    const long long rows = (long long)B * H * Nq;
+    if (rows > 0x7fffffffLL * 8) return FA_ERR_SHAPE;   // combine grid
+
+    FaParams p;
+    p.q = (const uint16_t *)q;
+    p.k = (const uint16_t *)k;
+    p.v = (const uint16_t *)v;
+    p.o = (uint16_t *)o;
+    p.lse = lse;
+    p.H = H;
+    p.Nq = Nq;
+    p.Nk = Nk;
+    p.nqt = (int)(((long long)Nq + 255) / 256);
+    p.nwork = (int)pl.work_items;
+    p.per_xcd = (int)((pl.work_items + 7) / 8);
+    const float LOG2E = 1.4426950408889634f;
+    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
+    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
+    p.fold = 0;
+    p.nsplit = pl.nsplit;
+    p.part_o = (float *)workspace;
+    p.part_ml = p.part_o + (size_t)pl.nsplit * rows * D;
+    hipStream_t st = (hipStream_t)stream;
+
+    hipError_t e;
+    const int key = (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
+    switch (key) {
+        case 0: e = launch_splitkv<0, 64, false>(p, pl.grid_x, rows, st); break;
+        case 1: e = launch_splitkv<0, 64, true>(p, pl.grid_x, rows, st); break;
+        case 2: e = launch_splitkv<0, 128, false>(p, pl.grid_x, rows, st); break;
+        case 3: e = launch_splitkv<0, 128, true>(p, pl.grid_x, rows, st); break;
+        case 4: e = launch_splitkv<1, 64, false>(p, pl.grid_x, rows, st); break;
+        case 5: e = launch_splitkv<1, 64, true>(p, pl.grid_x, rows, st); break;
+        case 6: e = launch_splitkv<1, 128, false>(p, pl.grid_x, rows, st); break;
+        case 7: e = launch_splitkv<1, 128, true>(p, pl.grid_x, rows, st); break;
+        default: return FA_ERR_SHAPE;
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return FA_ERR_LAUNCH;
+    }
+    return FA_OK;
+}
+
 const char *fa_strerror(int code) {
     switch (code) {
         case FA_OK: return "success";
@@ -738,11 +937,13 @@ const char *fa_strerror(int code) {
         case FA_ERR_SCALE: return "scale must be finite";
         case FA_ERR_ALIGN: return "q, k, v, o must be 16-byte aligned and lse 4-byte aligned";
         case FA_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
+        case FA_ERR_WORKSPACE: return "workspace is NULL or smaller than fa_fwd_splitkv_plan reports";
+        case FA_ERR_NSPLIT: return "nsplit exceeds 1024";
         default: return "unknown error code";
     }
 }
 
-int fa_version(void) { return 100; }
+int fa_version(void) { return 200; }
 
 int fa_last_hip_error(void) { return g_last_hip_error; }
 

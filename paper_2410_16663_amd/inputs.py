@@ -87,6 +87,12 @@ CONFIGS = {
 }
 
 
+# The decoding shape (appendix C of the paper: one new query per sequence against the cached keys
+# and values) at a LLaMA-7B-like head layout, batch 2, 32768 cached tokens: the workload the
+# split-KV entry point is measured on.  Not one of the five benchmark configurations.
+DECODE = Config("DEC", 6, 2, 32, 1, 32768, 128, BF16, True)
+
+
 def normal_bits(shape, seed: int, dtype: int, mult: float = 1.0) -> np.ndarray:
     """i.i.d. N(0,1)*mult drawn in fp32 from PCG64(seed), rounded once to the storage format."""
     rng = np.random.Generator(np.random.PCG64(seed))

@@ -30,11 +30,11 @@ def test_library_exports_every_declared_symbol(lib):
 def test_version_and_error_strings(lib):
     assert fa.fa_version() >= 100
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -10, -1):
         s = fa.fa_strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 10
     assert fa.fa_strerror(-99) == "unknown error code"
 
 
@@ -60,6 +60,47 @@ def test_argument_errors_come_back_before_any_launch(lib, change, code):
     with pytest.raises(fa.FaError) as e:
         fa.fa_fwd(**args)
     assert e.value.code == code
+
+
+SPLITKV_GOOD = dict(GOOD, Nq=1, Nk=4096, nsplit=0, workspace=0x6000, workspace_bytes=1 << 30)
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(q=0), fa.FA_ERR_NULL), (dict(lse=0), fa.FA_ERR_NULL),
+    (dict(Nk=0), fa.FA_ERR_SHAPE), (dict(D=96), fa.FA_ERR_HEADDIM), (dict(dtype=3), fa.FA_ERR_DTYPE),
+    (dict(scale=float("nan")), fa.FA_ERR_SCALE), (dict(v=0x3004), fa.FA_ERR_ALIGN),
+    (dict(workspace=0), fa.FA_ERR_WORKSPACE), (dict(workspace_bytes=16), fa.FA_ERR_WORKSPACE),
+    (dict(workspace=0x6008), fa.FA_ERR_ALIGN), (dict(nsplit=1025), fa.FA_ERR_NSPLIT),
+])
+def test_splitkv_argument_errors_come_back_before_any_launch(lib, change, code):
+    args = dict(SPLITKV_GOOD)
+    args.update(change)
+    assert fa.fa_fwd_splitkv_raw(**args) == code
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_fwd_splitkv(**args)
+    assert e.value.code == code
+
+
+def test_splitkv_plan(lib):
+    # given nsplit: kept, clamped to the number of 64-key tiles
+    p = fa.fa_fwd_splitkv_plan(2, 4, 1, 64 * 100, 128, 1, 0, 7)
+    assert (p.nsplit, p.grid_x, p.grid_y, p.work_items) == (7, 8, 7, 8)
+    assert p.workspace_bytes == 7 * 2 * 4 * 1 * (128 + 2) * 4
+    assert p.combine_grid == 1                                   # 8 rows, 8 rows per block at D = 128
+    assert fa.fa_fwd_splitkv_plan(1, 1, 1, 130, 64, 0, 0, 50).nsplit == 3
+    assert fa.fa_fwd_splitkv_plan(1, 1, 40, 130, 64, 0, 0, 1).combine_grid == 3   # 16 rows per block at D = 64
+    # chosen: 256 workgroups, runs of at least four tiles, at least one run
+    assert fa.fa_fwd_splitkv_plan(1, 32, 1, 32768, 128, 1, 1).nsplit == 8
+    assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 128, 1, 1).nsplit == 1
+    assert fa.fa_fwd_splitkv_plan(2, 24, 1, 32768, 128, 1, 1).nsplit == 6        # ceil(256 / 48)
+    assert fa.fa_fwd_splitkv_plan(1, 8, 1, 2048, 128, 1, 1).nsplit == 8          # 32 tiles / 4
+    assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 64, 1, 1).nsplit == 2         # D = 64: 512 workgroups
+    assert fa.fa_fwd_splitkv_plan(1, 1, 1, 100, 128, 1, 1).nsplit == 1
+    assert fa.fa_fwd_splitkv_plan(64, 32, 300, 4096, 128, 1, 1).nsplit == 1      # enough work items already
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_fwd_splitkv_plan(1, 1, 1, 100, 128, 1, 1, 2000)
+    assert e.value.code == fa.FA_ERR_NSPLIT
+    assert fa.load().fa_fwd_splitkv_plan(1, 1, 8, 8, 64, 0, 0, 0, None) == fa.FA_ERR_NULL
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
@@ -173,7 +214,8 @@ def test_build_report_shows_register_only_kernels():
     """Every kernel instantiation fits two waves per SIMD and touches no scratch memory."""
     from paper_2410_16663_amd import build
     build.build(force=True)
-    assert len(build.last_report) == 16          # 2 dtypes x 2 head dims x causal x mode
+    # attention: 2 dtypes x 2 head dims x causal x (split, wide, wide + split-KV); combine: 2 dtypes x 2 head dims
+    assert len(build.last_report) == 24 + 4
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

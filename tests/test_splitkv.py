@@ -1,0 +1,130 @@
+"""GPU parity of fa_fwd_splitkv (few queries against a long K/V, appendix C's decoding shape):
+against the CPU fp64 oracle element by element, and against fa_fwd itself.
+
+Same tolerances as fa_fwd: O max-abs 1e-2, O mean-abs 1e-3, LSE 1e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2410_16663_amd import inputs as I
+from gpu_util import check_against_oracle, run_fa_fwd, run_fa_fwd_splitkv
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_bits(rng, shape, dtype, mult=1.0):
+    return I.f32_to_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(mult), dtype)
+
+
+# B, H, Nq, Nk, D
+DECODE_SHAPES = [
+    (2, 3, 1, 1000, 128), (1, 2, 1, 4097, 64), (1, 4, 1, 20000, 128), (1, 1, 1, 63, 64), (3, 2, 2, 777, 128),
+]
+CHUNK_SHAPES = [
+    (1, 2, 37, 1500, 128), (1, 2, 300, 2000, 64), (1, 1, 512, 512, 128), (2, 1, 100, 6000, 64),
+]
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nsplit", [0, 1, 3, 16, 1024])
+@pytest.mark.parametrize("shape", DECODE_SHAPES)
+def test_decode_shapes_elementwise(oracle, shape, nsplit, causal, dtype):
+    B, H, Nq, Nk, D = shape
+    print(f"case splitkv decode shape={shape} nsplit={nsplit} causal={causal} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, causal, dtype)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
+    o, lse, plan = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
+    assert 1 <= plan.nsplit <= (Nk + 63) // 64
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} nsplit={nsplit} causal={causal} dt={dtype}")
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nsplit", [0, 2, 5, 13])
+@pytest.mark.parametrize("shape", CHUNK_SHAPES)
+def test_chunked_prefill_shapes_elementwise(oracle, shape, nsplit, causal, dtype):
+    """Several query rows (and query blocks) per head; causal runs end on the diagonal at different tiles
+    for different waves, and some runs of the early query blocks are empty."""
+    B, H, Nq, Nk, D = shape
+    print(f"case splitkv chunk shape={shape} nsplit={nsplit} causal={causal} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, causal, dtype, 1)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
+    o, lse, _ = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} nsplit={nsplit} causal={causal} dt={dtype}")
+
+
+def test_rows_without_visible_keys(oracle):
+    """Causal with Nq > Nk: the first rows see nothing in any run -> o = 0, lse = -inf."""
+    print("case splitkv empty rows", flush=True)
+    rng = np.random.default_rng(178)
+    q, k, v = (rand_bits(rng, (1, 2, n, 128), I.BF16) for n in (300, 200, 200))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, 0.1, True, I.BF16)
+    assert np.isneginf(lse_ref[:, :, :100]).all()
+    o, lse, plan = run_fa_fwd_splitkv(q, k, v, 0.1, True, I.BF16, 3)
+    assert plan.nsplit == 3
+    check_against_oracle(o, lse, o_ref, lse_ref, I.BF16, "empty rows")
+    assert (I.bits_to_f64(o, I.BF16)[:, :, :100] == 0).all()
+
+
+@pytest.mark.parametrize("scale", [-0.3, 0.0, 2.0])
+def test_unusual_scales_and_large_logits(oracle, scale):
+    """Large logits: the runs end with very different exponent references, which the merge must reconcile."""
+    print(f"case splitkv scale={scale}", flush=True)
+    rng = np.random.default_rng(179)
+    q, k, v = (rand_bits(rng, (1, 2, n, 64), I.F16, m) for n, m in ((5, 2.0), (3000, 2.0), (3000, 1.0)))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, I.F16)
+    o, lse, _ = run_fa_fwd_splitkv(q, k, v, scale, True, I.F16, 9)
+    check_against_oracle(o, lse, o_ref, lse_ref, I.F16, f"scale={scale}")
+
+
+def test_one_dominant_key_in_one_run():
+    """A key whose logit towers over the rest: the row is that key's value whichever run holds it (exact:
+    every other weight underflows to zero)."""
+    print("case splitkv dominant key", flush=True)
+    rng = np.random.default_rng(180)
+    Nk, D = 5000, 128
+    q, k, v = (rand_bits(rng, (1, 1, n, D), I.F16, 0.1) for n in (1, Nk, Nk))
+    for pos in (0, 2111, Nk - 1):
+        kk = k.copy()
+        kk[0, 0, pos] = I.f32_to_bits(I.bits_to_f64(q[0, 0, 0], I.F16).astype(np.float32) * 1000, I.F16)
+        o, lse, _ = run_fa_fwd_splitkv(q, kk, v, 1.0, False, I.F16, 11)
+        assert np.array_equal(o[0, 0, 0], v[0, 0, pos]), pos
+
+
+def test_matches_fa_fwd_and_ignores_workspace_contents(monkeypatch):
+    """Same inputs through both entry points: equal up to fp32 rounding order; a larger, NaN-filled
+    workspace changes nothing; one run (nsplit = 1) walks the tiles exactly as fa_fwd's wide mode does."""
+    print("case splitkv vs fa_fwd", flush=True)
+    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    rng = np.random.default_rng(181)
+    for dtype in (I.F16, I.BF16):
+        q, k, v = (rand_bits(rng, (2, 2, n, 128), dtype) for n in (70, 3000, 3000))
+        o0, lse0 = run_fa_fwd(q, k, v, 0.09, True, dtype)
+        o1, lse1, _ = run_fa_fwd_splitkv(q, k, v, 0.09, True, dtype, 1)
+        assert np.array_equal(o0, o1) and np.array_equal(lse0, lse1)
+        o2, lse2, _ = run_fa_fwd_splitkv(q, k, v, 0.09, True, dtype, 6)
+        o3, lse3, _ = run_fa_fwd_splitkv(q, k, v, 0.09, True, dtype, 6, extra_workspace=4096)
+        assert np.array_equal(o2, o3) and np.array_equal(lse2, lse3)
+        d = np.abs(I.bits_to_f64(o0, dtype) - I.bits_to_f64(o2, dtype))
+        assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2) and np.abs(lse0 - lse2).max() <= 1e-5
+
+
+def test_decode_at_cache_size_on_sampled_heads(oracle):
+    """The decoding workload bench.py times (inputs.DECODE, same seeded tensors, library-chosen nsplit):
+    every head is run, a sample of them is checked."""
+    cfg = I.DECODE
+    print("case splitkv " + cfg.describe(), flush=True)
+    q, k, v = I.make_qkv(cfg)
+    o, lse, plan = run_fa_fwd_splitkv(q, k, v, cfg.scale, cfg.causal, cfg.dtype, 0)
+    assert plan.nsplit == 4 and plan.grid_x * plan.grid_y == 256
+    for b, h in ((0, 0), (1, 17), (1, 31), (0, 8)):
+        o_ref, lse_ref = oracle.attention_fwd(q[b:b + 1, h:h + 1], k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1],
+                                              cfg.scale, cfg.causal, cfg.dtype)
+        check_against_oracle(o[b:b + 1, h:h + 1], lse[b:b + 1, h:h + 1], o_ref, lse_ref, cfg.dtype, f"head {b},{h}")
