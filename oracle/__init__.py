@@ -42,6 +42,10 @@ def _load():
         lib.fa_oracle_probs.restype = ctypes.c_int
         lib.fa_oracle_probs.argtypes = [u16p, u16p, f64p] + [ctypes.c_int] * 5 + [
             ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int64]
+        lib.fa_oracle_fwd_masked.restype = ctypes.c_int
+        lib.fa_oracle_fwd_masked.argtypes = [u16p, u16p, u16p, f64p, f64p] + [ctypes.c_int] * 5 + [
+            ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int32),
+            ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
         lib.fa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -91,6 +95,43 @@ def attention_fwd(q_bits, k_bits, v_bits, scale, causal, dtype, rows=None, nthre
                            float(scale), int(bool(causal)), int(dtype), rp, nr, int(nthreads))
     if rc != 0:
         raise RuntimeError(f"fa_oracle_fwd failed with code {rc}")
+    return o, lse
+
+
+def attention_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None, rows=None,
+                         nthreads=0):
+    """Oracle forward under a mask given by a descriptor: key j is visible to row i of batch entry b iff
+    ``j < kv_len[b]`` (all keys if ``kv_len`` is None) and (``j < prefix`` or
+    ``diag - left <= j <= diag + right``), ``diag = i + Nk - Nq``; a negative ``left`` / ``right`` is no limit.
+    Same shapes and return values as :func:`attention_fwd`."""
+    lib = _load()
+    B, H, Nq, D = q_bits.shape
+    Nk = k_bits.shape[2]
+    q = _u16(q_bits, (B, H, Nq, D))
+    k = _u16(k_bits, (B, H, Nk, D))
+    v = _u16(v_bits, (B, H, Nk, D))
+    if rows is None:
+        o = np.empty((B, H, Nq, D), dtype=np.float64)
+        lse = np.empty((B, H, Nq), dtype=np.float64)
+        rp, nr = None, 0
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        o = np.empty((rows.size, D), dtype=np.float64)
+        lse = np.empty((rows.size,), dtype=np.float64)
+        rp, nr = _ptr(rows, ctypes.c_int64), rows.size
+    if kv_len is None:
+        lp = None
+    else:
+        kv_len = np.ascontiguousarray(kv_len, dtype=np.int32)
+        if kv_len.shape != (B,):
+            raise ValueError("kv_len must have one entry per batch element")
+        lp = _ptr(kv_len, ctypes.c_int32)
+    rc = lib.fa_oracle_fwd_masked(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16), _ptr(v, ctypes.c_uint16),
+                                  _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double), B, H, Nq, Nk, D,
+                                  float(scale), int(left), int(right), int(prefix), lp, int(dtype), rp, nr,
+                                  int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"fa_oracle_fwd_masked failed with code {rc}")
     return o, lse
 
 

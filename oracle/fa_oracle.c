@@ -196,6 +196,101 @@ int fa_oracle_probs(const uint16_t *q, const uint16_t *k, double *p, int B, int 
     return 0;
 }
 
+/*
+ * Masks generated from a compact descriptor instead of a stored matrix (the idea of section
+ * 4.1's mask generator, taken beyond the lower-triangular case): query row i of batch entry b
+ * attends to key j exactly when
+ *     j < klen_b                              (klen_b = kv_len[b], or Nk if kv_len is NULL:
+ *                                              keys at and after klen_b are padding)
+ *     and ( j < prefix                        (a prefix every row sees, prefix-LM)
+ *           or  diag_i - left <= j <= diag_i + right )   with diag_i = i + (Nk - Nq),
+ *                                              a negative left / right meaning "no limit"
+ * left < 0, right = 0, prefix = 0, no kv_len is the causal mask; left < 0, right < 0 is no mask.
+ * Same plain row-at-a-time evaluation as fa_oracle_fwd, written out on its own: the logits of
+ * the visible keys, their maximum, the weights, the weighted sum.
+ */
+static int key_is_visible(int64_t i, int64_t j, int Nq, int Nk, int64_t left, int64_t right,
+                          int64_t prefix, int64_t klen) {
+    if (j >= klen) return 0;
+    if (j < prefix) return 1;
+    int64_t diag = i + ((int64_t)Nk - (int64_t)Nq);
+    if (left >= 0 && j < diag - left) return 0;
+    if (right >= 0 && j > diag + right) return 0;
+    return 1;
+}
+
+int fa_oracle_fwd_masked(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
+                         int B, int H, int Nq, int Nk, int D, double scale, int64_t left, int64_t right,
+                         int64_t prefix, const int32_t *kv_len, int dtype, const int64_t *rows,
+                         int64_t nrows, int nthreads) {
+    int err = bad_args(q, k, v, B, H, Nq, Nk, D, dtype);
+    if (err) return err;
+    if (!o || !lse) return -1;
+    if (prefix < 0) return -2;
+    int64_t total = rows ? nrows : (int64_t)B * H * Nq;
+    widen_init();
+    if (rows) {
+        for (int64_t r = 0; r < nrows; ++r)
+            if (rows[r] < 0 || rows[r] >= (int64_t)B * H * Nq) return -2;
+    }
+    if (kv_len) {
+        for (int b = 0; b < B; ++b)
+            if (kv_len[b] < 0 || kv_len[b] > Nk) return -2;
+    }
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)Nk);
+        if (!s) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t r = 0; r < total; ++r) {
+            if (!s) continue;
+            int64_t flat = rows ? rows[r] : r;
+            int64_t i = flat % Nq;
+            int64_t bh = flat / Nq;
+            int64_t klen = kv_len ? kv_len[bh / H] : Nk;
+            const uint16_t *q_row = q + flat * D;
+            const uint16_t *k_head = k + bh * (int64_t)Nk * D;
+            const uint16_t *v_head = v + bh * (int64_t)Nk * D;
+            double *o_row = o + r * D;
+            /* logits of the visible keys and their maximum */
+            double m = -INFINITY;
+            int64_t count = 0;
+            for (int64_t j = 0; j < Nk; ++j) {
+                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen)) continue;
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d) dot += widen(q_row[d], dtype) * widen(k_head[j * D + d], dtype);
+                s[j] = scale * dot;
+                if (s[j] > m) m = s[j];
+                ++count;
+            }
+            for (int d = 0; d < D; ++d) o_row[d] = 0.0;
+            if (count == 0) {
+                lse[r] = -INFINITY;
+                continue;
+            }
+            /* weights, their sum, the weighted sum of the value rows */
+            double l = 0.0;
+            for (int64_t j = 0; j < Nk; ++j) {
+                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen)) continue;
+                double w = exp(s[j] - m);
+                l += w;
+                for (int d = 0; d < D; ++d) o_row[d] += w * widen(v_head[j * D + d], dtype);
+            }
+            for (int d = 0; d < D; ++d) o_row[d] /= l;
+            lse[r] = m + log(l);
+        }
+        free(s);
+    }
+    return failed ? -8 : 0;
+}
+
 int fa_oracle_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
