@@ -133,12 +133,48 @@ def decode_entry(I, torch, fa, steps, warmup):
                          "bytes_per_call": kv_bytes}}
 
 
+def sliding_entry(I, torch, fa, steps, warmup):
+    """A causal sliding window through the descriptor-mask entry point, priced against the MFMA peak with the
+    exact number of attending (query, key) pairs: 4*D flop each."""
+    c = I.SLIDING
+    tq, tk, tv = device_inputs_on_gpu(c, torch)
+    dev = tq.device
+    to = torch.empty((c.B, c.H, c.Nq, c.D), dtype=torch.int16, device=dev)
+    tl = torch.empty((c.B, c.H, c.Nq), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+
+    def launch():
+        fa.fa_fwd_masked(tq, tk, tv, to, tl, c.B, c.H, c.Nq, c.Nk, c.D, c.scale, c.window - 1, 0, 0, None, c.dtype, sp)
+
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        launch()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    tf = c.flops() / (ms * 1e-3) / 1e12
+    return {"workload": c.describe(), "entry_point": "fa_fwd_masked", "ms_per_launch": round(ms, 4), "steps": steps,
+            "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
+            "flop_convention": "4*D per attending (query, key) pair, counted exactly",
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic("masked_SWA"),
+                         "kernel": "fa_fwd_kernel (wide, descriptor mask)", "flops_per_launch": c.flops()}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
+    ap.add_argument("--sliding-only", action="store_true",
+                    help="time only the sliding-window workload through fa_fwd_masked (for profiling runs)")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
@@ -171,6 +207,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.sliding_only:
+        print(json.dumps({"sliding": sliding_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
+        return
     if args.decode_only:
         print(json.dumps({"decode": decode_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
         return
@@ -236,6 +275,8 @@ def main():
         del tensors
         torch.cuda.empty_cache()
         extra["DEC"] = decode_entry(I, torch, fa, 50, 5)
+        torch.cuda.empty_cache()
+        extra["SWA"] = sliding_entry(I, torch, fa, 10, 2)
         out["other_workloads"] = extra
 
     print(json.dumps(out), flush=True)

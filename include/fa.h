@@ -27,6 +27,7 @@ extern "C" {
 #define FA_ERR_LAUNCH   -7 /* the HIP runtime rejected the launch (see fa_last_hip_error) */
 #define FA_ERR_WORKSPACE -8 /* fa_fwd_splitkv: workspace NULL or smaller than fa_fwd_splitkv_plan reports */
 #define FA_ERR_NSPLIT   -9 /* fa_fwd_splitkv: nsplit > 1024 */
+#define FA_ERR_MASK     -10 /* fa_fwd_masked: prefix < 0, or a key count outside 0..Nk */
 
 #define FA_DTYPE_F16  0 /* IEEE binary16 */
 #define FA_DTYPE_BF16 1 /* bfloat16 */
@@ -139,6 +140,73 @@ typedef struct fa_splitkv_plan {
  */
 int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, int nsplit,
                         fa_splitkv_plan_t *plan);
+
+/*
+ * Masks generated from a descriptor.  Section 4.1 replaces the stored S x S lower-triangular
+ * mask by a generator that yields any tile's mask on demand, and treats tiles that are
+ * entirely masked (skipped) or entirely visible (no mask applied) specially.  The same scheme,
+ * with an index predicate as the generator, covers the other masks inference uses:
+ *
+ *   row i of batch entry b sees key j  iff   j < klen_b  and
+ *       ( j < prefix   or   diag_i - window_left <= j <= diag_i + window_right ),
+ *   diag_i = i + (Nk - Nq)   (the key on the bottom-right-aligned diagonal),
+ *   klen_b = kv_len[b], or Nk when kv_len is NULL.
+ *
+ *   window_left  : keys before diag_i a row still sees;  < 0: no limit
+ *   window_right : keys after diag_i a row still sees;   < 0: no limit
+ *                  (-1, 0) is the causal mask, (-1, -1) no mask, (W-1, 0) a causal sliding
+ *                  window of W keys, (W, W) a symmetric local window
+ *   prefix       : >= 0; the first `prefix` keys are visible to every row whatever the window
+ *                  (prefix-LM: a bidirectional prompt followed by causal text)
+ *   kv_len       : DEVICE pointer to B int32 (4-byte aligned) or NULL: keys at and after
+ *                  kv_len[b] are padding; values are clamped to 0..Nk on the device
+ */
+typedef struct fa_mask {
+    int window_left;
+    int window_right;
+    int prefix;
+    const int *kv_len;
+} fa_mask_t;
+
+/*
+ * fa_fwd_masked -- fa_fwd under a descriptor mask.  Arguments, layouts, ownership, results
+ * (rows that see no key: o = 0, lse = -inf) and error behaviour as for fa_fwd; `mask` is a HOST
+ * pointer, read during the call only.  Needs Nq + Nk < 2^30.  One kernel, no workspace.  Per
+ * wave (32 query rows) and 64-key tile the kernel classifies the tile from the descriptor:
+ * nothing visible -> not computed; everything visible -> no mask work; otherwise the predicate
+ * is evaluated per element.  A workgroup (256 rows) only walks the prefix tiles and the tiles its
+ * rows' windows touch.
+ */
+int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *lse,
+                  int B, int H, int Nq, int Nk, int D, float scale, const fa_mask_t *mask, int dtype,
+                  void *stream);
+
+/*
+ * The tile classification and the workgroup's walk, callable on the host (the kernel runs the
+ * same code): for tests and for callers that want to know the work a mask leaves.
+ * kv_len here is ONE batch entry's key count (host int, 0..Nk); mask->kv_len is not read.
+ *
+ * fa_mask_tile_class: rows row_first..row_last against keys key_first..key_first+63 (key_first a
+ *   multiple of 64).  Returns
+ *   FA_TILE_SKIP (certainly nothing visible), FA_TILE_FULL (certainly everything visible, and all
+ *   64 keys exist), FA_TILE_PARTIAL (anything else), or a negative FA_ERR_* code.
+ * fa_mask_tile_walk: the 64-key tiles a workgroup owning rows row_first..row_last visits, in
+ *   order: tiles 0 .. *prefix_tiles-1, then *count - *prefix_tiles consecutive tiles starting at
+ *   *window_first_tile.  Every tile holding a key visible to one of the rows is among them.
+ * fa_mask_interior_run: within the walk of the workgroup owning rows wg_row_first..wg_row_last, the
+ *   positions [*first, *first + *count) that the wave owning rows row_first..row_last processes
+ *   without any check: each of those tiles is FA_TILE_FULL for the wave and the tile at the next
+ *   position exists and lies wholly inside K/V.  *first and *count are even; *count may be 0.
+ */
+#define FA_TILE_SKIP    0
+#define FA_TILE_FULL    1
+#define FA_TILE_PARTIAL 2
+int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk,
+                       int row_first, int row_last, int key_first);
+int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
+                      int *prefix_tiles, int *window_first_tile, int *count);
+int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int wg_row_first, int wg_row_last,
+                         int row_first, int row_last, int *first, int *count);
 
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);

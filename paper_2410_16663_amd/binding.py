@@ -22,6 +22,10 @@ FA_ERR_ALIGN = -6
 FA_ERR_LAUNCH = -7
 FA_ERR_WORKSPACE = -8
 FA_ERR_NSPLIT = -9
+FA_ERR_MASK = -10
+FA_TILE_SKIP = 0
+FA_TILE_FULL = 1
+FA_TILE_PARTIAL = 2
 FA_DTYPE_F16 = 0
 FA_DTYPE_BF16 = 1
 FA_MODE_SPLIT = 0
@@ -29,8 +33,8 @@ FA_MODE_WIDE = 1
 FA_MODE_WIDE_FOLD = 2
 
 # every symbol include/fa.h declares
-EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_strerror", "fa_version",
-           "fa_last_hip_error")
+EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_mask_tile_class",
+           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_strerror", "fa_version", "fa_last_hip_error")
 
 _lib = None
 
@@ -48,6 +52,12 @@ class FaSplitKvPlan(ctypes.Structure):
     _fields_ = [("nsplit", ctypes.c_int), ("grid_x", ctypes.c_int), ("grid_y", ctypes.c_int),
                 ("combine_grid", ctypes.c_int), ("work_items", ctypes.c_longlong),
                 ("workspace_bytes", ctypes.c_longlong)]
+
+
+class FaMask(ctypes.Structure):
+    """fa_mask_t of include/fa.h (kv_len is a device address or 0)."""
+    _fields_ = [("window_left", ctypes.c_int), ("window_right", ctypes.c_int), ("prefix", ctypes.c_int),
+                ("kv_len", ctypes.c_void_p)]
 
 
 class FaError(RuntimeError):
@@ -76,6 +86,16 @@ def load() -> ctypes.CDLL:
             ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_longlong, vp]
         lib.fa_fwd_splitkv_plan.restype = ctypes.c_int
         lib.fa_fwd_splitkv_plan.argtypes = [ctypes.c_int] * 8 + [ctypes.POINTER(FaSplitKvPlan)]
+        ip = ctypes.POINTER(ctypes.c_int)
+        lib.fa_fwd_masked.restype = ctypes.c_int
+        lib.fa_fwd_masked.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
+            ctypes.c_float, ctypes.POINTER(FaMask), ctypes.c_int, vp]
+        lib.fa_mask_tile_class.restype = ctypes.c_int
+        lib.fa_mask_tile_class.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 6
+        lib.fa_mask_tile_walk.restype = ctypes.c_int
+        lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ip, ip]
+        lib.fa_mask_interior_run.restype = ctypes.c_int
+        lib.fa_mask_interior_run.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 7 + [ip, ip]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -143,6 +163,57 @@ def fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, dtype, nsplit=0) -> FaSplitKvPl
     if rc != FA_OK:
         raise FaError(rc)
     return plan
+
+
+def _mask(left, right, prefix, kv_len):
+    return FaMask(int(left), int(right), int(prefix), _addr(kv_len) or None)
+
+
+def fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0) -> int:
+    """Call fa_fwd_masked (mask fields passed one by one) and return its status code unchanged."""
+    m = _mask(left, right, prefix, kv_len)
+    return load().fa_fwd_masked(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nq),
+                                int(Nk), int(D), float(scale), ctypes.byref(m), int(dtype), _addr(stream))
+
+
+def fa_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0) -> None:
+    """fa_fwd_masked of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last, key_first) -> int:
+    """fa_mask_tile_class of include/fa.h (host only; kv_len is one batch entry's key count)."""
+    m = _mask(left, right, prefix, None)
+    rc = load().fa_mask_tile_class(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last),
+                                   int(key_first))
+    if rc < 0:
+        raise FaError(rc)
+    return rc
+
+
+def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last):
+    """fa_mask_tile_walk of include/fa.h (host only): the list of tile indices, in the order walked."""
+    m = _mask(left, right, prefix, None)
+    np_, base, count = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = load().fa_mask_tile_walk(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last),
+                                  ctypes.byref(np_), ctypes.byref(base), ctypes.byref(count))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return list(range(np_.value)) + [base.value + i for i in range(count.value - np_.value)]
+
+
+def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_row_last, row_first, row_last):
+    """fa_mask_interior_run of include/fa.h (host only): (first, count) in positions of the workgroup's walk."""
+    m = _mask(left, right, prefix, None)
+    first, count = ctypes.c_int(), ctypes.c_int()
+    rc = load().fa_mask_interior_run(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(wg_row_first),
+                                     int(wg_row_last), int(row_first), int(row_last), ctypes.byref(first),
+                                     ctypes.byref(count))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return first.value, count.value
 
 
 def fa_strerror(code: int) -> str:

@@ -71,7 +71,76 @@ struct FaParams {
     int nsplit;
     float *part_o;  // [nsplit][B*H*Nq][D]
     float *part_ml; // [nsplit][B*H*Nq][2]: reference (log2 units), row sum relative to it
+    // descriptor masks only (see MaskGeom): window limits with "no limit" already replaced by
+    // MASK_NO_LIMIT, the prefix clamped to Nk, per-batch key counts or nullptr
+    int left, right, prefix;
+    const int *kv_len;
 };
+
+// ---- masks generated from a descriptor (section 4.1's generator beyond the triangular case).
+// Row i of a batch entry with klen valid keys sees key j iff
+//     j < pfx  or  ( i + off - left <= j <= min(klen - 1, i + off + right) ),
+// with off = Nk - Nq and pfx = min(prefix, klen).  The kernel never evaluates this per element
+// unless it has to: per wave (32 rows) and 64-key tile it first classifies the tile, exactly the
+// three cases of section 4.1 -- nothing visible: skipped; everything visible: no mask work;
+// otherwise: the predicate per element.  Shared by the kernel and the host-side entry points
+// that expose it to tests.
+constexpr int MASK_NO_LIMIT = 1 << 30;   // window limit standing for "none" (needs Nq + Nk < 2^30)
+struct MaskGeom {
+    int off, left, right, pfx, klen;
+};
+enum { TILE_SKIP = 0, TILE_FULL = 1, TILE_PARTIAL = 2 };
+
+// Classification of 64-key tile t for rows r0..r1 (r0 <= r1), reduced to comparisons of t against
+// limits that depend on the rows only (computed once per wave): with k0 = 64 t,
+//   some key in a window   <=>  k0 <= r1 + off + right  and  k0 + 63 >= r0 + off - left
+//   every key in every window <=> k0 >= r1 + off - left  and  k0 + 63 <= r0 + off + right
+//   some / every key in the prefix <=> k0 < pfx  /  k0 + 63 < pfx;   every key exists <=> k0 + 63 < klen
+// (x >> 6 is the floor of x / 64 for negative x too).  TILE_SKIP and TILE_FULL are only returned
+// when they are certain; TILE_PARTIAL may be returned for a tile that is in fact all visible or all
+// masked.
+struct RowTiles {
+    int any_lo, any_hi;     // tiles any_lo..any_hi hold a key of some row's window
+    int all_lo, all_hi;     // tiles all_lo..all_hi lie inside every row's window
+    int pfx_any, pfx_all;   // tiles below pfx_any hold a prefix key, tiles below pfx_all only prefix keys
+    int exist_any, exist_all;   // tiles below exist_any hold an existing key, below exist_all only existing keys
+};
+__host__ __device__ inline RowTiles row_tiles(const MaskGeom &g, int r0, int r1) {
+    RowTiles w;
+    w.any_lo = (r0 + g.off - g.left) >> 6;
+    w.any_hi = (r1 + g.off + g.right) >> 6;
+    if (r0 + g.off - g.left >= g.klen) w.any_hi = w.any_lo - 1;   // every window starts in the padding: none
+    w.all_lo = (r1 + g.off - g.left + 63) >> 6;
+    w.all_hi = (r0 + g.off + g.right - 63) >> 6;
+    w.pfx_any = (g.pfx + 63) >> 6;
+    w.pfx_all = g.pfx >> 6;
+    w.exist_any = (g.klen + 63) >> 6;
+    w.exist_all = g.klen >> 6;
+    return w;
+}
+__host__ __device__ inline int tile_class(const RowTiles &w, int t) {
+    if (t >= w.exist_any) return TILE_SKIP;
+    if (!(t < w.pfx_any) && !(t >= w.any_lo && t <= w.any_hi)) return TILE_SKIP;
+    if (t < w.exist_all && (t < w.pfx_all || (t >= w.all_lo && t <= w.all_hi))) return TILE_FULL;
+    return TILE_PARTIAL;
+}
+
+// The tiles a workgroup owning rows R0..R1 walks: the prefix tiles 0 .. np-1, then `count - np`
+// consecutive tiles from `base` on (the rows' window); when the two runs touch or overlap they are
+// one run from tile 0.  Position j of the walk is tile (j < np ? j : base + j - np).
+struct TileSeq {
+    int np, base, count;
+};
+__host__ __device__ inline TileSeq tile_sequence(const MaskGeom &g, int R0, int R1) {
+    constexpr int BNK = 64;
+    const int p_t = (g.pfx + BNK - 1) / BNK;
+    const int lo_key = max(0, R0 + g.off - g.left);
+    const int hi_key = min(g.klen - 1, R1 + g.off + g.right);
+    if (hi_key < lo_key) return {p_t, 0, p_t};
+    const int w_lo = lo_key / BNK, w_hi = hi_key / BNK;
+    if (w_lo <= p_t) return {0, 0, max(p_t, w_hi + 1)};
+    return {p_t, w_lo, p_t + (w_hi - w_lo + 1)};
+}
 
 // Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into
 // 32-row blocks; the blocks are taken in 8 rounds of G (= workgroups per head) consecutive
@@ -82,6 +151,31 @@ struct FaParams {
 __host__ __device__ inline int fold_block(int G, int g, int w) {
     const int r = w < 4 ? 7 - w : w - 4;
     return r * G + ((r & 1) ? (G - 1 - g) : g);
+}
+
+// The run of positions [first, first + count) of a workgroup's walk that a wave (row limits w) can
+// take without any check: every tile of the run is TILE_FULL for the wave, and the tile at the
+// next position exists in the walk and lies wholly inside K/V (it is loaded unconditionally).
+// `first` and `count` are even (the two tile buffers alternate).  Of the two candidates -- the
+// tiles inside every row's window, the tiles made of prefix keys only -- the longer one.
+struct Run {
+    int first, count;
+};
+__host__ __device__ inline Run interior_run(const RowTiles &w, const TileSeq &sq, int Nk) {
+    const int phys = Nk / 64 - 2;                     // last tile t such that tile t+1 is wholly inside K/V
+    // window candidate, as tiles t0..t1 inclusive, restricted to the window part of the walk
+    int t0 = max(w.all_lo, sq.np > 0 ? sq.base : 0);
+    int t1 = min(min(w.all_hi, w.exist_all - 1), phys);
+    int a0 = t0 - sq.base + sq.np, a1 = t1 - sq.base + sq.np + 1;   // positions [a0, a1)
+    a1 = min(a1, sq.count - 1);
+    // prefix candidate: positions = tiles 0 .. p1-1
+    int p1 = min(min(w.pfx_all, w.exist_all), phys + 1);
+    p1 = min(p1, (sq.np > 0 ? sq.np : sq.count) - 1);
+    Run r = {0, 0};
+    a0 = (a0 + 1) & ~1;
+    if (a1 - a0 >= 2) r = {a0, (a1 - a0) & ~1};
+    if (p1 >= 2 && (p1 & ~1) > r.count) r = {0, p1 & ~1};
+    return r;
 }
 
 constexpr int BN = 64;  // keys per tile
@@ -180,9 +274,12 @@ __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, u
 //   the result is left unnormalised in p.part_o / p.part_ml for fa_combine_kernel.  The shape for
 //   few queries against a long K/V (decoding, chunked prefill), where batch x heads x query
 //   blocks alone cannot fill the chip.
-template <int DT, int D, bool CAUSAL, bool WIDE, bool SPLITKV = false>
+// GENMASK = true (wide only, CAUSAL = false): the mask comes from the descriptor in p (window,
+//   prefix, per-batch key count) instead of the causal flag; see MaskGeom.
+template <int DT, int D, bool CAUSAL, bool WIDE, bool SPLITKV = false, bool GENMASK = false>
 __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     static_assert(WIDE || !SPLITKV, "split-KV is built on the wide decomposition");
+    static_assert(!GENMASK || (WIDE && !SPLITKV && !CAUSAL), "descriptor masks are built on the plain wide decomposition");
     constexpr int NWL = WIDE ? 8 : 4;             // waves that load one tile together
     constexpr int BM = WIDE ? 256 : 128;          // query rows per workgroup
     constexpr int TSTEP = WIDE ? 1 : 2;           // a group's consecutive tiles are TSTEP apart
@@ -215,7 +312,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     const int wi = (blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
     if (wi >= p.nwork) return;
     const int bh = wi / p.nqt;
-    const int qt = CAUSAL ? (p.nqt - 1 - wi % p.nqt) : (wi % p.nqt);
+    const int qt = (CAUSAL || GENMASK) ? (p.nqt - 1 - wi % p.nqt) : (wi % p.nqt);
 
     const int Nq = p.Nq, Nk = p.Nk;
     const int off = Nk - Nq;
@@ -245,10 +342,38 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         nt = (int)((long long)(blockIdx.y + 1) * nt_all / p.nsplit) - t_lo;
     }
     // group-local tile j is global tile t_lo + TSTEP*j + grp
-    const int nj_loop = (nt + TSTEP - 1) / TSTEP;            // tiles of group 0 (>= those of group 1)
+    int nj_loop = (nt + TSTEP - 1) / TSTEP;                  // tiles of group 0 (>= those of group 1)
     int n_act = 0;                                           // group tiles this wave works on
     if (q_wave < Nq && kmax_wave >= 0 && kmax_wave / BN >= grp) n_act = (kmax_wave / BN - grp) / TSTEP + 1;
     if constexpr (SPLITKV) n_act = max(n_act - t_lo, 0);
+    // descriptor masks: the workgroup's walk and this wave's rows
+    MaskGeom mg = {off, 0, 0, 0, Nk};
+    TileSeq seq = {0, 0, 0};
+    RowTiles wt = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (GENMASK) {
+        int klen = Nk;
+        if (p.kv_len) klen = min(max(p.kv_len[bh / p.H], 0), Nk);
+        klen = __builtin_amdgcn_readfirstlane(klen);
+        mg = {off, p.left, p.right, min(p.prefix, klen), klen};
+        seq = tile_sequence(mg, qt * BM, last_row_wg);
+        if (q_wave < Nq) wt = row_tiles(mg, q_wave, min(q_wave + 31, Nq - 1));   // else: exist_any = 0, every tile is skipped
+        nt = seq.count;
+        nj_loop = nt;
+    }
+    // position j of this group's walk -> tile index
+    auto tile_of = [&](int j) __attribute__((always_inline)) -> int {
+        if constexpr (GENMASK) return j < seq.np ? j : seq.base + (j - seq.np);
+        return t_lo + TSTEP * j + grp;
+    };
+    // ... -> does this wave work on it, and does it need the per-element predicate
+    int cls_cur = TILE_PARTIAL;
+    auto classify = [&](int j) __attribute__((always_inline)) -> bool {
+        if constexpr (GENMASK) {
+            cls_cur = tile_class(wt, tile_of(j));
+            return cls_cur != TILE_SKIP;
+        }
+        return j < n_act;
+    };
 
     const size_t kv_head = (size_t)bh * Nk * D;
     const unsigned char *kgb = (const unsigned char *)(p.k + kv_head);
@@ -316,8 +441,8 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     };
     // group tile j lives in buffer j % NSTAGE
     // full_c: the caller knows the tile lies wholly inside K/V (no check, no clamped path)
-    auto load_k = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(kgb, t_lo + TSTEP * j + grp, st * TILEB, std::true_type{}, full_c); };
-    auto load_v = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(vgb, t_lo + TSTEP * j + grp, (NSTAGE + st) * TILEB, std::false_type{}, full_c); };
+    auto load_k = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(kgb, tile_of(j), st * TILEB, std::true_type{}, full_c); };
+    auto load_v = [&](int j, int st, auto full_c) __attribute__((always_inline)) { load_tile(vgb, tile_of(j), (NSTAGE + st) * TILEB, std::false_type{}, full_c); };
 
     // ---- operand fragments.  K fragment (mb, kb): rows = keys mb*32 + l32, 8 contiguous d.
     auto k_frag = [&](const unsigned char *ks, int mb, int kb) __attribute__((always_inline)) -> s16x8 {
@@ -390,10 +515,26 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- softmax of group tile j: logits in sreg -> packed exponentials in pf, running sums
     auto softmax_cluster = [&](int j, auto maybe_masked_c) __attribute__((always_inline)) {
         {
-            const int k0 = (t_lo + TSTEP * j + grp) * BN;
+            const int k0 = tile_of(j) * BN;
             // mask only when the tile straddles the diagonal or the end of K
-            const bool need_mask = decltype(maybe_masked_c)::value &&
+            const bool need_mask = decltype(maybe_masked_c)::value && !GENMASK &&
                                    ((k0 + BN - 1 >= Nk) || (CAUSAL && (k0 + BN - 1 > q_wave + off)));
+            if (GENMASK && decltype(maybe_masked_c)::value && cls_cur == TILE_PARTIAL) {
+                // limits relative to this lane's first key of the tile, so that each element compares
+                // a constant against them (nothing per element lives across tiles)
+                const int kb0 = k0 + 4 * h;
+                const int lo = qrow + off - mg.left - kb0;
+                const int hi = min(mg.klen - 1, qrow + off + mg.right) - kb0;
+                const int pf = mg.pfx - kb0;
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int c = mb * 32 + 8 * (r >> 2) + (r & 3);
+                        const bool vis = (c < pf) | ((c >= lo) & (c <= hi));   // no short-circuit: selects, not branches
+                        sreg[mb][r] = vis ? sreg[mb][r] : -INFINITY;
+                    }
+            }
             if (need_mask) {
                 int lim = Nk - 1;
                 if (CAUSAL) lim = min(lim, qrow + off);
@@ -494,7 +635,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         constexpr int ST = decltype(st_c)::value;             // j % NSTAGE
         constexpr int ST_LOAD = (ST + PD) % NSTAGE;           // (j + PD) % NSTAGE
         const bool issued = TSTEP * (j + PD) + grp < nt;
-        if (j < n_act) {
+        if (classify(j)) {
             // the loads go out between the two matrix clusters (measured 1% better than up front:
             // their LDS writes then land mostly during the softmax, when no wave reads LDS);
             // split-KV waits on HBM, not on LDS: there they go out first
@@ -543,6 +684,16 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     }
     int j = 0;
     if constexpr (NSTAGE == 2) {
+        if constexpr (GENMASK && D == 64) j_int = 0;   // a third copy of the loop body costs D = 64 its fourth wave per SIMD
+        if constexpr (GENMASK && D == 128) {
+            // descriptor masks: the check-free run may start anywhere (a window's lower edge comes first)
+            const Run run = interior_run(wt, seq, Nk);
+            for (; j < run.first; j += 2) {
+                iteration(integral_constant<int, 0>{}, j);
+                iteration(integral_constant<int, 1>{}, j + 1);
+            }
+            j_int = run.first + run.count;
+        }
         for (; j < j_int; j += 2) {
             interior(integral_constant<int, 0>{}, j);
             interior(integral_constant<int, 1>{}, j + 1);
@@ -670,6 +821,12 @@ hipError_t launch(const FaParams &p, int nwork_padded, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int DT, int D>
+hipError_t launch_masked(const FaParams &p, int nwork_padded, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, false, true, false, true>), dim3(nwork_padded), dim3(512), 0, stream, p);
+    return hipGetLastError();
+}
+
 template <int DT, int D, bool CAUSAL>
 hipError_t launch_splitkv(const FaParams &p, int nwork_padded, long long rows, hipStream_t stream) {
     hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, true, true>), dim3(nwork_padded, p.nsplit), dim3(512), 0, stream, p);
@@ -759,6 +916,21 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
     return (int)n;
 }
 
+// Descriptor checks shared by the masked entry points; fills the geometry for `klen` valid keys.
+int mask_geometry(const fa_mask_t *mask, int klen, int Nq, int Nk, MaskGeom *g) {
+    if (!mask) return FA_ERR_NULL;
+    if (Nq <= 0 || Nk <= 0) return FA_ERR_SHAPE;
+    if ((long long)Nq + Nk >= MASK_NO_LIMIT) return FA_ERR_SHAPE;   // window arithmetic stays inside int
+    if (mask->prefix < 0) return FA_ERR_MASK;
+    if (klen < 0 || klen > Nk) return FA_ERR_MASK;
+    g->off = Nk - Nq;
+    g->left = mask->window_left < 0 || mask->window_left > MASK_NO_LIMIT ? MASK_NO_LIMIT : mask->window_left;
+    g->right = mask->window_right < 0 || mask->window_right > MASK_NO_LIMIT ? MASK_NO_LIMIT : mask->window_right;
+    g->pfx = mask->prefix < klen ? mask->prefix : klen;
+    g->klen = klen;
+    return FA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -819,6 +991,8 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     p.nsplit = 1;
     p.part_o = nullptr;
     p.part_ml = nullptr;
+    p.left = p.right = p.prefix = 0;
+    p.kv_len = nullptr;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
@@ -902,6 +1076,8 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
     p.fold = 0;
+    p.left = p.right = p.prefix = 0;
+    p.kv_len = nullptr;
     p.nsplit = pl.nsplit;
     p.part_o = (float *)workspace;
     p.part_ml = p.part_o + (size_t)pl.nsplit * rows * D;
@@ -927,6 +1103,97 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     return FA_OK;
 }
 
+int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
+                  int D, float scale, const fa_mask_t *mask, int dtype, void *stream) {
+    if (!q || !k || !v || !o || !lse || !mask) return FA_ERR_NULL;
+    const int rc = check_shape(B, H, Nq, Nk, D, dtype);
+    if (rc != FA_OK) return rc;
+    if (!isfinite(scale)) return FA_ERR_SCALE;
+    MaskGeom g;
+    const int mrc = mask_geometry(mask, Nk, Nq, Nk, &g);
+    if (mrc != FA_OK) return mrc;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
+    if (((uintptr_t)lse | (uintptr_t)mask->kv_len) & 3) return FA_ERR_ALIGN;
+
+    const long long nqt = ((long long)Nq + 255) / 256;
+    const long long nwork = (long long)B * H * nqt;
+    FaParams p;
+    p.q = (const uint16_t *)q;
+    p.k = (const uint16_t *)k;
+    p.v = (const uint16_t *)v;
+    p.o = (uint16_t *)o;
+    p.lse = lse;
+    p.H = H;
+    p.Nq = Nq;
+    p.Nk = Nk;
+    p.nqt = (int)nqt;
+    p.nwork = (int)nwork;
+    p.per_xcd = (int)((nwork + 7) / 8);
+    const float LOG2E = 1.4426950408889634f;
+    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
+    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
+    p.fold = 0;
+    p.nsplit = 1;
+    p.part_o = nullptr;
+    p.part_ml = nullptr;
+    p.left = g.left;
+    p.right = g.right;
+    p.prefix = mask->prefix < Nk ? mask->prefix : Nk;
+    p.kv_len = mask->kv_len;
+    const int grid = p.per_xcd * 8;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    switch ((dtype << 1) | (D == 128)) {
+        case 0: e = launch_masked<0, 64>(p, grid, st); break;
+        case 1: e = launch_masked<0, 128>(p, grid, st); break;
+        case 2: e = launch_masked<1, 64>(p, grid, st); break;
+        case 3: e = launch_masked<1, 128>(p, grid, st); break;
+        default: return FA_ERR_SHAPE;
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return FA_ERR_LAUNCH;
+    }
+    return FA_OK;
+}
+
+int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last, int key_first) {
+    MaskGeom g;
+    const int rc = mask_geometry(mask, kv_len, Nq, Nk, &g);
+    if (rc != FA_OK) return rc;
+    if (row_first < 0 || row_last < row_first || row_last >= Nq || key_first < 0 || key_first >= Nk) return FA_ERR_SHAPE;
+    if (key_first % BN) return FA_ERR_SHAPE;
+    return tile_class(row_tiles(g, row_first, row_last), key_first / BN);
+}
+
+int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
+                      int *prefix_tiles, int *window_first_tile, int *count) {
+    if (!prefix_tiles || !window_first_tile || !count) return FA_ERR_NULL;
+    MaskGeom g;
+    const int rc = mask_geometry(mask, kv_len, Nq, Nk, &g);
+    if (rc != FA_OK) return rc;
+    if (row_first < 0 || row_last < row_first || row_last >= Nq) return FA_ERR_SHAPE;
+    const TileSeq sq = tile_sequence(g, row_first, row_last);
+    *prefix_tiles = sq.np;
+    *window_first_tile = sq.base;
+    *count = sq.count;
+    return FA_OK;
+}
+
+int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int wg_row_first, int wg_row_last,
+                         int row_first, int row_last, int *first, int *count) {
+    if (!first || !count) return FA_ERR_NULL;
+    MaskGeom g;
+    const int rc = mask_geometry(mask, kv_len, Nq, Nk, &g);
+    if (rc != FA_OK) return rc;
+    if (wg_row_first < 0 || wg_row_last < wg_row_first || wg_row_last >= Nq) return FA_ERR_SHAPE;
+    if (row_first < wg_row_first || row_last < row_first || row_last > wg_row_last) return FA_ERR_SHAPE;
+    const Run r = interior_run(row_tiles(g, row_first, row_last), tile_sequence(g, wg_row_first, wg_row_last), Nk);
+    *first = r.first;
+    *count = r.count;
+    return FA_OK;
+}
+
 const char *fa_strerror(int code) {
     switch (code) {
         case FA_OK: return "success";
@@ -939,6 +1206,7 @@ const char *fa_strerror(int code) {
         case FA_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
         case FA_ERR_WORKSPACE: return "workspace is NULL or smaller than fa_fwd_splitkv_plan reports";
         case FA_ERR_NSPLIT: return "nsplit exceeds 1024";
+        case FA_ERR_MASK: return "mask descriptor: prefix must be >= 0 and a key count within 0..Nk";
         default: return "unknown error code";
     }
 }

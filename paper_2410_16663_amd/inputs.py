@@ -49,6 +49,7 @@ class Config:
     dtype: int
     causal: bool
     mult: float = 1.0  # inputs are N(0,1) * mult
+    window: int = 0    # > 0 (with causal): each row sees only the last `window` visible keys
 
     @property
     def scale(self) -> float:
@@ -64,10 +65,15 @@ class Config:
             return self.B * self.H * self.Nq * self.Nk
         off = self.Nk - self.Nq
         i = np.arange(self.Nq, dtype=np.int64)
-        return int(self.B * self.H * np.clip(i + off + 1, 0, self.Nk).sum())
+        n = np.clip(i + off + 1, 0, self.Nk)
+        if self.window > 0:
+            n = np.minimum(n, self.window)
+        return int(self.B * self.H * n.sum())
 
     def flops(self) -> float:
         """4*B*H*Nq*Nk*D, halved when causal (the benchmark's FLOP convention)."""
+        if self.window > 0:
+            return 4.0 * self.D * self.visible_pairs()   # windowed: the exact count of attending pairs
         f = 4.0 * self.B * self.H * self.Nq * self.Nk * self.D
         return f / 2 if self.causal else f
 
@@ -75,6 +81,7 @@ class Config:
         dt = "fp16" if self.dtype == F16 else "bf16"
         return (f"{self.name}: B={self.B} H={self.H} Nq={self.Nq} Nk={self.Nk} D={self.D} {dt} "
                 f"{'causal' if self.causal else 'non-causal'}"
+                + (f" window={self.window}" if self.window > 0 else "")
                 + (f" inputs x{self.mult:g}" if self.mult != 1.0 else ""))
 
 
@@ -91,6 +98,11 @@ CONFIGS = {
 # and values) at a LLaMA-7B-like head layout, batch 2, 32768 cached tokens: the workload the
 # split-KV entry point is measured on.  Not one of the five benchmark configurations.
 DECODE = Config("DEC", 6, 2, 32, 1, 32768, 128, BF16, True)
+
+# A causal sliding window (each token attends to the last 4096 tokens) over a 16384-token prefill at the
+# same head layout: the workload the descriptor-mask entry point is measured on.  Not one of the five
+# benchmark configurations either.
+SLIDING = Config("SWA", 7, 2, 32, 16384, 16384, 128, BF16, True, 1.0, 4096)
 
 
 def normal_bits(shape, seed: int, dtype: int, mult: float = 1.0) -> np.ndarray:

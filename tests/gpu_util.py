@@ -53,6 +53,25 @@ def run_fa_fwd_splitkv(q_bits, k_bits, v_bits, scale, causal, dtype, nsplit=0, e
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy(), plan
 
 
+def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None):
+    """Same as run_fa_fwd through fa_fwd_masked; kv_len (list of B ints or None) is copied to the GPU."""
+    import torch
+    assert torch.cuda.is_available()
+    B, H, Nq, D = q_bits.shape
+    Nk = k_bits.shape[2]
+    dev = torch.device("cuda:0")
+    tq = torch.from_numpy(q_bits.view(np.int16)).to(dev)
+    tk = torch.from_numpy(k_bits.view(np.int16)).to(dev)
+    tv = torch.from_numpy(v_bits.view(np.int16)).to(dev)
+    to = torch.full((B, H, Nq, D), 0x7E00 if dtype == I.F16 else 0x7FC0, dtype=torch.int16, device=dev)
+    tl = torch.full((B, H, Nq), float("nan"), dtype=torch.float32, device=dev)
+    tlen = None if kv_len is None else torch.tensor(list(kv_len), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    fa.fa_fwd_masked(tq, tk, tv, to, tl, B, H, Nq, Nk, D, scale, left, right, prefix, tlen, dtype, stream)
+    torch.cuda.synchronize()
+    return to.cpu().numpy().view(np.uint16), tl.cpu().numpy()
+
+
 def bf16_half_ulp(x):
     """Half a unit in the last place of bfloat16 (8 significant bits) at magnitude |x|."""
     ax = np.maximum(np.abs(x), 2.0 ** -126)

@@ -1,0 +1,163 @@
+"""Host-side checks of the descriptor-mask logic the kernel runs (tile classification and the
+workgroup's walk, exposed through the C ABI), by brute force against explicit keep-matrices, and the
+argument errors of fa_fwd_masked.  No GPU needed."""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2410_16663_amd import binding as fa
+
+BN = 64
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return fa.load()
+
+
+def keep_matrix(Nq, Nk, left, right, prefix, klen):
+    """The predicate of include/fa.h, written out per element."""
+    i = np.arange(Nq)[:, None]
+    j = np.arange(Nk)[None, :]
+    diag = i + (Nk - Nq)
+    win = np.ones((Nq, Nk), dtype=bool)
+    if left >= 0:
+        win &= j >= diag - left
+    if right >= 0:
+        win &= j <= diag + right
+    return (j < klen) & ((j < prefix) | win)
+
+
+DESCRIPTORS = [
+    # left, right, prefix
+    (-1, 0, 0), (-1, -1, 0), (100, 0, 0), (0, 0, 0), (63, 0, 0), (64, 0, 0), (200, 30, 0), (-1, 70, 0), (40, -1, 0),
+    (-1, 0, 130), (90, 0, 64), (10, 10, 1), (0, 0, 500), (-1, 0, 10**6), (2**31 - 1, 2**31 - 1, 0),
+]
+SHAPES = [(300, 300), (130, 700), (700, 130), (1, 500), (257, 64), (64, 65)]
+
+
+@pytest.mark.parametrize("Nq,Nk", SHAPES)
+@pytest.mark.parametrize("left,right,prefix", DESCRIPTORS)
+def test_tile_class_is_never_wrong_and_exact_where_it_must_be(lib, left, right, prefix, Nq, Nk):
+    for klen in sorted({Nk, max(Nk - 37, 0), min(64, Nk), 0}):
+        keep = keep_matrix(Nq, Nk, left, right, prefix, klen)
+        for r0 in range(0, Nq, 32):                       # a wave's 32 rows
+            r1 = min(r0 + 31, Nq - 1)
+            for k0 in range(0, Nk, BN):
+                blk = keep[r0:r1 + 1, k0:k0 + BN]
+                cls = fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, k0)
+                if cls == fa.FA_TILE_SKIP:
+                    assert not blk.any(), (r0, k0, klen)
+                elif cls == fa.FA_TILE_FULL:
+                    assert blk.all() and blk.shape[1] == BN, (r0, k0, klen)
+                else:
+                    assert cls == fa.FA_TILE_PARTIAL
+                # without a prefix the classification is exact: a mixed tile is the only partial one
+                if prefix == 0:
+                    want = fa.FA_TILE_SKIP if not blk.any() else (
+                        fa.FA_TILE_FULL if blk.all() and blk.shape[1] == BN else fa.FA_TILE_PARTIAL)
+                    assert cls == want, (r0, k0, klen, cls, want)
+
+
+@pytest.mark.parametrize("Nq,Nk", SHAPES)
+@pytest.mark.parametrize("left,right,prefix", DESCRIPTORS)
+def test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk):
+    ntiles = (Nk + BN - 1) // BN
+    for klen in sorted({Nk, max(Nk - 37, 0), 0}):
+        keep = keep_matrix(Nq, Nk, left, right, prefix, klen)
+        for R0 in range(0, Nq, 256):                      # a workgroup's 256 rows
+            R1 = min(R0 + 255, Nq - 1)
+            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1)
+            assert len(set(walk)) == len(walk) and all(0 <= t < ntiles for t in walk)
+            assert all(t * BN < klen for t in walk)       # never a tile of pure padding
+            needed = {t for t in range(ntiles) if keep[R0:R1 + 1, t * BN:(t + 1) * BN].any()}
+            assert needed <= set(walk)
+            # the walk is the prefix tiles plus one contiguous run: at most the gap-free hull of what is needed
+            if needed and prefix == 0:
+                assert set(walk) == set(range(min(needed), max(needed) + 1))
+
+
+@pytest.mark.parametrize("Nq,Nk", SHAPES + [(1024, 1024), (300, 1100)])
+@pytest.mark.parametrize("left,right,prefix", DESCRIPTORS + [(300, 0, 0), (400, 100, 0), (-1, 0, 300), (500, 0, 256)])
+def test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk):
+    for klen in sorted({Nk, max(Nk - 37, 0), 0}):
+        for R0 in range(0, Nq, 256):
+            R1 = min(R0 + 255, Nq - 1)
+            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1)
+            for r0 in range(R0, R1 + 1, 32):
+                r1 = min(r0 + 31, Nq - 1)
+                first, count = fa.fa_mask_interior_run(left, right, prefix, klen, Nq, Nk, R0, R1, r0, r1)
+                assert first % 2 == 0 and count % 2 == 0 and first >= 0 and count >= 0
+                assert first + count <= max(len(walk) - 1, 0)        # a next position always exists
+                cls = [fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, t * BN) for t in walk]
+                for j in range(first, first + count):
+                    assert cls[j] == fa.FA_TILE_FULL, (klen, R0, r0, j)
+                    assert (walk[j + 1] + 1) * BN <= Nk, (klen, R0, r0, j)   # loaded without a bounds check
+                # it is not needlessly short: the longest run of FULL tiles (with a loadable successor) is at most
+                # three positions longer (two for evenness at either end, one for the successor)
+                ok = [c == fa.FA_TILE_FULL and j + 1 < len(walk) and (walk[j + 1] + 1) * BN <= Nk
+                      for j, c in enumerate(cls)]
+                best = cur = 0
+                for x in ok:
+                    cur = cur + 1 if x else 0
+                    best = max(best, cur)
+                if prefix == 0 or left < 0:      # (a prefix run and a window run that touch are not joined)
+                    assert count >= best - 3, (klen, R0, r0, first, count, best)
+
+
+def test_causal_walk_matches_the_causal_plan(lib):
+    """(-1, 0) walks what fa_fwd's wide mode walks for the same rows."""
+    Nq = Nk = 2048
+    for R0 in range(0, Nq, 256):
+        walk = fa.fa_mask_tile_walk(-1, 0, 0, Nk, Nq, Nk, R0, R0 + 255)
+        assert walk == list(range((R0 + 255) // BN + 1))
+    total = sum(len(fa.fa_mask_tile_walk(-1, 0, 0, Nk, Nq, Nk, R0, R0 + 255)) for R0 in range(0, Nq, 256))
+    import os
+    os.environ["FA_FWD_MODE"] = "wide"
+    try:
+        assert total == fa.fa_fwd_plan(1, 1, Nq, Nk, 128, 1, 0).tiles_visited
+    finally:
+        del os.environ["FA_FWD_MODE"]
+
+
+def test_sliding_window_walk_is_short(lib):
+    """A causal window of W keys: each 256-row workgroup walks about (W + 256) / 64 tiles, whatever N is."""
+    N, W = 32768, 4096
+    for R0 in (0, 8192, N - 256):
+        walk = fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, R0, R0 + 255)
+        lo, hi = max(0, R0 - (W - 1)) // BN, (R0 + 255) // BN
+        assert walk == list(range(lo, hi + 1))
+    assert len(fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, 8192, 8192 + 255)) == (W + 256) // BN
+
+
+GOOD = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, Nq=8, Nk=8, D=64, scale=0.125,
+            left=-1, right=0, prefix=0, kv_len=0, dtype=0)
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(q=0), fa.FA_ERR_NULL), (dict(lse=0), fa.FA_ERR_NULL), (dict(Nq=0), fa.FA_ERR_SHAPE),
+    (dict(D=32), fa.FA_ERR_HEADDIM), (dict(dtype=5), fa.FA_ERR_DTYPE), (dict(scale=float("inf")), fa.FA_ERR_SCALE),
+    (dict(prefix=-1), fa.FA_ERR_MASK), (dict(kv_len=0x6002), fa.FA_ERR_ALIGN), (dict(o=0x4008), fa.FA_ERR_ALIGN),
+    (dict(Nq=2**30, Nk=64), fa.FA_ERR_SHAPE),
+])
+def test_masked_argument_errors_come_back_before_any_launch(lib, change, code):
+    args = dict(GOOD)
+    args.update(change)
+    assert fa.fa_fwd_masked_raw(**args) == code
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_fwd_masked(**args)
+    assert e.value.code == code
+
+
+def test_null_descriptor_and_bad_host_queries(lib):
+    L = fa.load()
+    assert L.fa_fwd_masked(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 8, 8, 64, 0.1, None, 0, None) == fa.FA_ERR_NULL
+    with pytest.raises(fa.FaError):
+        fa.fa_mask_tile_class(-1, 0, 0, 9, 8, 8, 0, 7, 0)        # key count beyond Nk
+    with pytest.raises(fa.FaError):
+        fa.fa_mask_tile_class(-1, 0, 0, 8, 8, 8, 0, 8, 0)        # row beyond Nq
+    with pytest.raises(fa.FaError):
+        fa.fa_mask_tile_class(-1, 0, 0, 8, 8, 128, 0, 7, 32)     # not a tile boundary
+    with pytest.raises(fa.FaError):
+        fa.fa_mask_tile_walk(-1, 0, -2, 8, 8, 8, 0, 7)

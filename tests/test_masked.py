@@ -1,0 +1,93 @@
+"""GPU parity of fa_fwd_masked (masks generated per tile from a descriptor: window, prefix, per-batch key
+counts) against the CPU fp64 oracle, element by element.
+
+Same tolerances as fa_fwd: O max-abs 1e-2, O mean-abs 1e-3, LSE 1e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2410_16663_amd import inputs as I
+from gpu_util import check_against_oracle, run_fa_fwd, run_fa_fwd_masked
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_bits(rng, shape, dtype, mult=1.0):
+    return I.f32_to_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(mult), dtype)
+
+
+# B, H, Nq, Nk, D: one and several workgroups per head, ragged tails, Nq != Nk both ways, decode
+SHAPES = [(1, 2, 300, 300, 128), (2, 2, 130, 700, 64), (1, 1, 700, 130, 128), (2, 1, 1, 500, 64), (1, 1, 1000, 1000, 64),
+          (2, 1, 520, 777, 128)]
+MASKS = [
+    # left, right, prefix, kv_len fraction of Nk per batch entry (None: no padding)
+    (-1, 0, 0, None), (-1, -1, 0, None), (100, 0, 0, None), (0, 0, 0, None), (63, 0, 0, None), (200, 30, 0, None),
+    (-1, 70, 0, None), (40, -1, 0, None), (-1, 0, 130, None), (90, 0, 64, None), (10, 10, 1, None), (0, 0, 500, None),
+    (-1, -1, 0, (0.5, 0.9)), (-1, 0, 0, (1.0, 0.3)), (150, 0, 70, (0.8, 0.05)), (-1, 0, 0, (0.0, 1.0)),
+]
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", MASKS)
+@pytest.mark.parametrize("shape", SHAPES)
+def test_descriptor_masks_elementwise(oracle, shape, mask, dtype):
+    B, H, Nq, Nk, D = shape
+    left, right, prefix, frac = mask
+    kv_len = None if frac is None else [int(round(f * Nk)) for f in (frac * B)[:B]]
+    print(f"case masked shape={shape} mask=({left},{right},{prefix},{kv_len}) dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, mask[:3], dtype)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} {mask} dt={dtype}")
+    empty = np.isneginf(lse_ref)
+    assert (I.bits_to_f64(o, dtype)[empty] == 0).all()
+
+
+def test_causal_and_unmasked_descriptors_equal_fa_fwd_bit_for_bit(monkeypatch):
+    """(-1, 0) and (-1, -1) walk the same tiles with the same arithmetic as fa_fwd's wide mode."""
+    print("case masked vs fa_fwd", flush=True)
+    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    rng = np.random.default_rng(401)
+    for dtype, D in ((I.F16, 64), (I.BF16, 128)):
+        q, k, v = (rand_bits(rng, (2, 2, n, D), dtype) for n in (600, 900, 900))
+        for causal, (left, right) in ((True, (-1, 0)), (False, (-1, -1))):
+            o0, l0 = run_fa_fwd(q, k, v, 0.1, causal, dtype)
+            o1, l1 = run_fa_fwd_masked(q, k, v, 0.1, dtype, left, right)
+            assert np.array_equal(o0, o1) and np.array_equal(l0, l1)
+
+
+def test_exact_special_cases():
+    """left = right = 0: every row is the value row on its diagonal, bit for bit; a key count of one: row = v[0]."""
+    print("case masked exact specials", flush=True)
+    rng = np.random.default_rng(402)
+    for dtype in (I.F16, I.BF16):
+        q, k, v = (rand_bits(rng, (1, 2, n, 64), dtype) for n in (200, 330, 330))
+        o, lse = run_fa_fwd_masked(q, k, v, 0.125, dtype, 0, 0)
+        assert np.array_equal(o, v[:, :, 130:])
+        o, lse = run_fa_fwd_masked(q, k, v, 0.125, dtype, -1, -1, 0, [1])
+        assert np.array_equal(o, np.broadcast_to(v[:, :, :1], o.shape))
+
+
+@pytest.mark.parametrize("scale", [-0.12, 0.0, 0.15])
+def test_unusual_scales(oracle, scale):
+    print(f"case masked scale={scale}", flush=True)
+    rng = np.random.default_rng(403)
+    q, k, v = (rand_bits(rng, (1, 2, n, 128), I.BF16) for n in (400, 400, 400))
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, I.BF16, 70, 0, 20)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, I.BF16, 70, 0, 20)
+    check_against_oracle(o, lse, o_ref, lse_ref, I.BF16, f"scale={scale}")
+
+
+def test_sliding_window_at_full_size_on_sampled_rows(oracle):
+    """The windowed workload bench.py times (inputs.SLIDING, same seeded tensors): a stratified sample of rows."""
+    cfg = I.SLIDING
+    print("case masked " + cfg.describe(), flush=True)
+    q, k, v = I.make_qkv(cfg)
+    o, lse = run_fa_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0)
+    rows = I.sample_rows(cfg, per_head=16)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0, rows=rows)
+    check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, "SWA sample")
