@@ -46,6 +46,9 @@ def _load():
         lib.fa_oracle_fwd_masked.argtypes = [u16p, u16p, u16p, f64p, f64p] + [ctypes.c_int] * 5 + [
             ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int32),
             ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
+        lib.fa_oracle_attn_linear.restype = ctypes.c_int
+        lib.fa_oracle_attn_linear.argtypes = [u16p, u16p, u16p, u16p, f64p] + [ctypes.c_int] * 6 + [
+            ctypes.c_double, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
         lib.fa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -133,6 +136,35 @@ def attention_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1
     if rc != 0:
         raise RuntimeError(f"fa_oracle_fwd_masked failed with code {rc}")
     return o, lse
+
+
+def attention_linear(q_bits, k_bits, v_bits, w_bits, scale, causal, dtype, rows=None, nthreads=0):
+    """Attention followed by the output projection: y[b,i,:] = concat_h(o[b,h,i,:]) @ w, everything in fp64.
+
+    w_bits [H*D, N] uint16 bit patterns.  Returns y [B,Nq,N], or [len(rows),N] for the flat token ids b*Nq+i."""
+    lib = _load()
+    B, H, Nq, D = q_bits.shape
+    Nk = k_bits.shape[2]
+    q = _u16(q_bits, (B, H, Nq, D))
+    k = _u16(k_bits, (B, H, Nk, D))
+    v = _u16(v_bits, (B, H, Nk, D))
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2 or w.shape[0] != H * D:
+        raise ValueError("w_bits must be uint16 [H*D, N]")
+    N = w.shape[1]
+    if rows is None:
+        y = np.empty((B, Nq, N), dtype=np.float64)
+        rp, nr = None, 0
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        y = np.empty((rows.size, N), dtype=np.float64)
+        rp, nr = _ptr(rows, ctypes.c_int64), rows.size
+    rc = lib.fa_oracle_attn_linear(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16), _ptr(v, ctypes.c_uint16),
+                                   _ptr(w, ctypes.c_uint16), _ptr(y, ctypes.c_double), B, H, Nq, Nk, D, N,
+                                   float(scale), int(bool(causal)), int(dtype), rp, nr, int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"fa_oracle_attn_linear failed with code {rc}")
+    return y
 
 
 def attention_probs(q_bits, k_bits, scale, causal, dtype, row):

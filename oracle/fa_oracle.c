@@ -291,6 +291,74 @@ int fa_oracle_fwd_masked(const uint16_t *q, const uint16_t *k, const uint16_t *v
     return failed ? -8 : 0;
 }
 
+/*
+ * Attention followed by the output projection (section 4.2: the attention and the Linear that
+ * follows it are computed together, block of rows by block of rows; appendix C: X_O contains
+ * Softmax(...) X_V W_O).  For token t = (b, i):
+ *     a[t, h*D + d] = o[b, h, i, d]            the heads' attention rows side by side
+ *     y[t, n]       = sum_c a[t, c] * w[c, n]  c = 0 .. H*D-1,  n = 0 .. N-1
+ * with o exactly as fa_oracle_fwd defines it, kept in fp64 (never rounded to 16 bits), and w a
+ * [H*D, N] matrix of 16-bit patterns, n fastest.  With the heads of one device this is that
+ * device's partial sum of the projection; the sum over devices (the AllReduce) is outside.
+ * rows == NULL: every token, y is [B, Nq, N]; else the nrows flat token ids b*Nq + i listed,
+ * y is [nrows, N].
+ */
+int fa_oracle_attn_linear(const uint16_t *q, const uint16_t *k, const uint16_t *v, const uint16_t *w,
+                          double *y, int B, int H, int Nq, int Nk, int D, int N, double scale,
+                          int causal, int dtype, const int64_t *rows, int64_t nrows, int nthreads) {
+    int err = bad_args(q, k, v, B, H, Nq, Nk, D, dtype);
+    if (err) return err;
+    if (!w || !y) return -1;
+    if (N <= 0) return -2;
+    int64_t total = rows ? nrows : (int64_t)B * Nq;
+    widen_init();
+    if (rows) {
+        for (int64_t r = 0; r < nrows; ++r)
+            if (rows[r] < 0 || rows[r] >= (int64_t)B * Nq) return -2;
+    }
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)Nk);
+        double *a = (double *)malloc(sizeof(double) * (size_t)H * D);
+        if (!s || !a) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t r = 0; r < total; ++r) {
+            if (!s || !a) continue;
+            int64_t t = rows ? rows[r] : r;
+            int64_t b = t / Nq, i = t % Nq;
+            int64_t n_vis = visible_count(i, Nq, Nk, causal);
+            /* the attention row of every head, side by side */
+            for (int h = 0; h < H; ++h) {
+                int64_t bh = b * H + h;
+                double *a_h = a + (int64_t)h * D;
+                for (int d = 0; d < D; ++d) a_h[d] = 0.0;
+                if (n_vis == 0) continue;
+                const uint16_t *v_head = v + bh * (int64_t)Nk * D;
+                double m, l;
+                row_weights(q + (bh * Nq + i) * D, k + bh * (int64_t)Nk * D, n_vis, D, scale, dtype, s, &m, &l);
+                for (int64_t j = 0; j < n_vis; ++j)
+                    for (int d = 0; d < D; ++d) a_h[d] += s[j] * widen(v_head[j * D + d], dtype);
+                for (int d = 0; d < D; ++d) a_h[d] /= l;
+            }
+            /* times the projection matrix */
+            double *y_row = y + r * N;
+            for (int n = 0; n < N; ++n) y_row[n] = 0.0;
+            for (int64_t c = 0; c < (int64_t)H * D; ++c)
+                for (int n = 0; n < N; ++n) y_row[n] += a[c] * widen(w[c * N + n], dtype);
+        }
+        free(s);
+        free(a);
+    }
+    return failed ? -8 : 0;
+}
+
 int fa_oracle_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

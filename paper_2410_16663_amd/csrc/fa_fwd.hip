@@ -59,6 +59,8 @@ struct FaParams {
     uint16_t *o;
     float *lse;
     int H, Nq, Nk;
+    int q_rows;     // rows between consecutive heads of q, o, lse in memory (>= Nq: the call may cover a row range)
+    int kv_rows;    // same for k, v (>= Nk)
     int nqt;        // query tiles per (b,h)
     int nwork;      // B*H*nqt
     int per_xcd;    // ceil(nwork / 8)
@@ -375,14 +377,14 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         return j < n_act;
     };
 
-    const size_t kv_head = (size_t)bh * Nk * D;
+    const size_t kv_head = (size_t)bh * p.kv_rows * D;
     const unsigned char *kgb = (const unsigned char *)(p.k + kv_head);
     const unsigned char *vgb = (const unsigned char *)(p.v + kv_head);
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds d = 16*kb + 8*h + 0..7 of its row
     s16x8 qf[KB];
     {
-        const uint16_t *qp = p.q + ((size_t)bh * Nq + (qrow < Nq ? qrow : 0)) * D + 8 * h;
+        const uint16_t *qp = p.q + ((size_t)bh * p.q_rows + (qrow < Nq ? qrow : 0)) * D + 8 * h;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             s16x8 x = *(const s16x8 *)(qp + kb * 16);
@@ -765,7 +767,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     }
     if (qrow < Nq) {
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        uint16_t *op = p.o + ((size_t)bh * Nq + qrow) * D + 4 * h;
+        uint16_t *op = p.o + ((size_t)bh * p.q_rows + qrow) * D + 4 * h;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -776,7 +778,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
                 *(s16x4 *)(op + db * 32 + 8 * g) = st;
             }
         if (h == 0)
-            p.lse[(size_t)bh * Nq + qrow] = l_tot > 0.f ? (m_ref + __log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+            p.lse[(size_t)bh * p.q_rows + qrow] = l_tot > 0.f ? (m_ref + __log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
     }
 }
 
@@ -916,6 +918,36 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
     return (int)n;
 }
 
+// The parameter block every entry point starts from: one launch over the whole of q (no row range,
+// no split, no descriptor mask).
+FaParams base_params(const void *q, const void *k, const void *v, void *o, float *lse, int H, int Nq, int Nk,
+                     long long nqt, long long nwork, float scale) {
+    FaParams p;
+    p.q = (const uint16_t *)q;
+    p.k = (const uint16_t *)k;
+    p.v = (const uint16_t *)v;
+    p.o = (uint16_t *)o;
+    p.lse = lse;
+    p.H = H;
+    p.Nq = Nq;
+    p.Nk = Nk;
+    p.q_rows = Nq;
+    p.kv_rows = Nk;
+    p.nqt = (int)nqt;
+    p.nwork = (int)nwork;
+    p.per_xcd = (int)((nwork + 7) / 8);
+    const float LOG2E = 1.4426950408889634f;
+    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
+    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
+    p.fold = 0;
+    p.nsplit = 1;
+    p.part_o = nullptr;
+    p.part_ml = nullptr;
+    p.left = p.right = p.prefix = 0;
+    p.kv_len = nullptr;
+    return p;
+}
+
 // Descriptor checks shared by the masked entry points; fills the geometry for `klen` valid keys.
 int mask_geometry(const fa_mask_t *mask, int klen, int Nq, int Nk, MaskGeom *g) {
     if (!mask) return FA_ERR_NULL;
@@ -972,27 +1004,8 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
 
-    FaParams p;
-    p.q = (const uint16_t *)q;
-    p.k = (const uint16_t *)k;
-    p.v = (const uint16_t *)v;
-    p.o = (uint16_t *)o;
-    p.lse = lse;
-    p.H = H;
-    p.Nq = Nq;
-    p.Nk = Nk;
-    p.nqt = (int)nqt;
-    p.nwork = (int)nwork;
-    p.per_xcd = (int)((nwork + 7) / 8);
-    const float LOG2E = 1.4426950408889634f;
-    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
-    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
+    FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, nqt, nwork, scale);
     p.fold = mode == FA_MODE_WIDE_FOLD;
-    p.nsplit = 1;
-    p.part_o = nullptr;
-    p.part_ml = nullptr;
-    p.left = p.right = p.prefix = 0;
-    p.kv_len = nullptr;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
@@ -1060,24 +1073,7 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     const long long rows = (long long)B * H * Nq;
     if (rows > 0x7fffffffLL * 8) return FA_ERR_SHAPE;   // combine grid
 
-    FaParams p;
-    p.q = (const uint16_t *)q;
-    p.k = (const uint16_t *)k;
-    p.v = (const uint16_t *)v;
-    p.o = (uint16_t *)o;
-    p.lse = lse;
-    p.H = H;
-    p.Nq = Nq;
-    p.Nk = Nk;
-    p.nqt = (int)(((long long)Nq + 255) / 256);
-    p.nwork = (int)pl.work_items;
-    p.per_xcd = (int)((pl.work_items + 7) / 8);
-    const float LOG2E = 1.4426950408889634f;
-    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
-    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
-    p.fold = 0;
-    p.left = p.right = p.prefix = 0;
-    p.kv_len = nullptr;
+    FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, ((long long)Nq + 255) / 256, pl.work_items, scale);
     p.nsplit = pl.nsplit;
     p.part_o = (float *)workspace;
     p.part_ml = p.part_o + (size_t)pl.nsplit * rows * D;
@@ -1117,25 +1113,7 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
 
     const long long nqt = ((long long)Nq + 255) / 256;
     const long long nwork = (long long)B * H * nqt;
-    FaParams p;
-    p.q = (const uint16_t *)q;
-    p.k = (const uint16_t *)k;
-    p.v = (const uint16_t *)v;
-    p.o = (uint16_t *)o;
-    p.lse = lse;
-    p.H = H;
-    p.Nq = Nq;
-    p.Nk = Nk;
-    p.nqt = (int)nqt;
-    p.nwork = (int)nwork;
-    p.per_xcd = (int)((nwork + 7) / 8);
-    const float LOG2E = 1.4426950408889634f;
-    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
-    p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
-    p.fold = 0;
-    p.nsplit = 1;
-    p.part_o = nullptr;
-    p.part_ml = nullptr;
+    FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, nqt, nwork, scale);
     p.left = g.left;
     p.right = g.right;
     p.prefix = mask->prefix < Nk ? mask->prefix : Nk;
