@@ -167,6 +167,52 @@ def sliding_entry(I, torch, fa, steps, warmup):
                          "kernel": "fa_fwd_kernel (wide, descriptor mask)", "flops_per_launch": c.flops()}}
 
 
+def projection_entry(I, torch, fa, steps, warmup):
+    """Attention + output projection per block of rows (fa_attn_linear), priced against the MFMA peak:
+    attention flop (causal convention) + 2 * tokens * (H*D) * N for the projection."""
+    import math
+    c = I.PROJECTION
+    n_out, rpb = I.PROJECTION_N, I.PROJECTION_ROWS_PER_BLOCK
+    tq, tk, tv = device_inputs_on_gpu(c, torch)
+    dev = tq.device
+    tdt = torch.float16 if c.dtype == 0 else torch.bfloat16
+    g = torch.Generator(device=dev)
+    g.manual_seed(c.seeds[2] + 1)
+    tw = (torch.randn((c.H * c.D, n_out), generator=g, device=dev, dtype=torch.float32)
+          / math.sqrt(c.H * c.D)).to(tdt).view(torch.int16)
+    to = torch.empty((c.B, c.H, c.Nq, c.D), dtype=torch.int16, device=dev)
+    tl = torch.empty((c.B, c.H, c.Nq), dtype=torch.float32, device=dev)
+    ty = torch.empty((c.B, c.Nq, n_out), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+
+    def launch():
+        fa.fa_attn_linear(tq, tk, tv, tw, to, tl, ty, c.B, c.H, c.Nq, c.Nk, c.D, n_out, c.scale, int(c.causal), c.dtype,
+                          rpb, sp)
+
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        launch()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    fl_attn = c.flops()
+    fl_proj = 2.0 * c.B * c.Nq * c.H * c.D * n_out
+    tf = (fl_attn + fl_proj) / (ms * 1e-3) / 1e12
+    return {"workload": c.describe() + f" + projection {c.H * c.D}x{n_out}, blocks of {rpb} rows (first one half)",
+            "entry_point": "fa_attn_linear", "ms_per_call": round(ms, 4), "steps": steps,
+            "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds); w ~ N(0,1)/sqrt(H*D)",
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                         "kernel": "fa_fwd_kernel + fa_linear_kernel, per block",
+                         "flops_per_call": fl_attn + fl_proj, "flops_attention": fl_attn, "flops_projection": fl_proj}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -175,6 +221,8 @@ def main():
     ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
     ap.add_argument("--sliding-only", action="store_true",
                     help="time only the sliding-window workload through fa_fwd_masked (for profiling runs)")
+    ap.add_argument("--projection-only", action="store_true",
+                    help="time only the attention + output projection workload (for profiling runs)")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
@@ -209,6 +257,9 @@ def main():
         del src, dst
     if args.sliding_only:
         print(json.dumps({"sliding": sliding_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
+        return
+    if args.projection_only:
+        print(json.dumps({"projection": projection_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
         return
     if args.decode_only:
         print(json.dumps({"decode": decode_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
@@ -277,6 +328,8 @@ def main():
         extra["DEC"] = decode_entry(I, torch, fa, 50, 5)
         torch.cuda.empty_cache()
         extra["SWA"] = sliding_entry(I, torch, fa, 10, 2)
+        torch.cuda.empty_cache()
+        extra["LIN"] = projection_entry(I, torch, fa, 10, 2)
         out["other_workloads"] = extra
 
     print(json.dumps(out), flush=True)

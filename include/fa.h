@@ -142,6 +142,38 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
                         fa_splitkv_plan_t *plan);
 
 /*
+ * fa_attn_linear_block -- attention followed by the output projection for ONE block of query rows
+ * (section 4.2: the attention and the Linear after it are computed together, block of rows by
+ * block of rows, so that the AllReduce of a finished block can run while the next block is
+ * computed).  For the rows row_first <= i < row_first + row_count of every batch entry:
+ *     o[b,h,i,:]  and lse[b,h,i]   exactly as fa_fwd gives them for the whole problem
+ *     y[b,i,n] = sum_{h,d} o[b,h,i,d] * w[h*D + d, n]       n = 0 .. N-1, fp32
+ * i.e. the heads' attention rows laid side by side times w (appendix C: Softmax(...) X_V W_O); with
+ * the heads of one device, y is that device's partial sum of the projection.
+ *
+ *   q, k, v, o, lse : as for fa_fwd (the FULL tensors; only the block's rows of o, lse are written)
+ *   w   : DEVICE pointer, [H*D, N] contiguous, N fastest, 16-bit elements of `dtype`, 16-byte aligned
+ *   y   : DEVICE pointer, [B, Nq, N] fp32; only the block's rows are written
+ *   N   : outputs per token, a positive multiple of 256
+ *   row_first, row_count : the block; 0 <= row_first, 1 <= row_count, row_first + row_count <= Nq
+ *
+ * Enqueues two kernels on `stream` (the attention of the block, then a GEMM that reads the
+ * attention output in its own [B,H,Nq,D] layout; o is rounded to `dtype` in between, products
+ * accumulate in fp32).  No allocation, no workspace, no synchronisation: a caller overlaps
+ * communication by enqueueing it on another stream behind an event recorded after this call.
+ * Calls for different blocks are independent.  Error behaviour as for fa_fwd.
+ *
+ * fa_attn_linear -- every block in order on one stream: blocks of rows_per_block rows, the first
+ * one half that size (nothing can overlap with the first block); rows_per_block <= 0: one block.
+ */
+int fa_attn_linear_block(const void *q, const void *k, const void *v, const void *w, void *o, float *lse,
+                         float *y, int B, int H, int Nq, int Nk, int D, int N, float scale, int causal,
+                         int dtype, int row_first, int row_count, void *stream);
+int fa_attn_linear(const void *q, const void *k, const void *v, const void *w, void *o, float *lse,
+                   float *y, int B, int H, int Nq, int Nk, int D, int N, float scale, int causal,
+                   int dtype, int rows_per_block, void *stream);
+
+/*
  * Masks generated from a descriptor.  Section 4.1 replaces the stored S x S lower-triangular
  * mask by a generator that yields any tile's mask on demand, and treats tiles that are
  * entirely masked (skipped) or entirely visible (no mask applied) specially.  The same scheme,

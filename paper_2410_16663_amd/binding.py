@@ -33,7 +33,8 @@ FA_MODE_WIDE = 1
 FA_MODE_WIDE_FOLD = 2
 
 # every symbol include/fa.h declares
-EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_mask_tile_class",
+EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
+           "fa_attn_linear", "fa_mask_tile_class",
            "fa_mask_tile_walk", "fa_mask_interior_run", "fa_strerror", "fa_version", "fa_last_hip_error")
 
 _lib = None
@@ -86,6 +87,10 @@ def load() -> ctypes.CDLL:
             ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_longlong, vp]
         lib.fa_fwd_splitkv_plan.restype = ctypes.c_int
         lib.fa_fwd_splitkv_plan.argtypes = [ctypes.c_int] * 8 + [ctypes.POINTER(FaSplitKvPlan)]
+        lib.fa_attn_linear_block.restype = ctypes.c_int
+        lib.fa_attn_linear_block.argtypes = [vp] * 7 + [ctypes.c_int] * 6 + [ctypes.c_float] + [ctypes.c_int] * 4 + [vp]
+        lib.fa_attn_linear.restype = ctypes.c_int
+        lib.fa_attn_linear.argtypes = [vp] * 7 + [ctypes.c_int] * 6 + [ctypes.c_float] + [ctypes.c_int] * 3 + [vp]
         ip = ctypes.POINTER(ctypes.c_int)
         lib.fa_fwd_masked.restype = ctypes.c_int
         lib.fa_fwd_masked.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
@@ -163,6 +168,32 @@ def fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, dtype, nsplit=0) -> FaSplitKvPl
     if rc != FA_OK:
         raise FaError(rc)
     return plan
+
+
+def fa_attn_linear_block_raw(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, row_first, row_count,
+                             stream=0) -> int:
+    """Call fa_attn_linear_block and return its status code unchanged."""
+    return load().fa_attn_linear_block(_addr(q), _addr(k), _addr(v), _addr(w), _addr(o), _addr(lse), _addr(y), int(B),
+                                       int(H), int(Nq), int(Nk), int(D), int(N), float(scale), int(causal),
+                                       int(dtype), int(row_first), int(row_count), _addr(stream))
+
+
+def fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, row_first, row_count,
+                         stream=0) -> None:
+    """fa_attn_linear_block of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_attn_linear_block_raw(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, row_first,
+                                  row_count, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_attn_linear(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, rows_per_block=0, stream=0) -> None:
+    """fa_attn_linear of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = load().fa_attn_linear(_addr(q), _addr(k), _addr(v), _addr(w), _addr(o), _addr(lse), _addr(y), int(B), int(H),
+                               int(Nq), int(Nk), int(D), int(N), float(scale), int(causal), int(dtype),
+                               int(rows_per_block), _addr(stream))
+    if rc != FA_OK:
+        raise FaError(rc)
 
 
 def _mask(left, right, prefix, kv_len):

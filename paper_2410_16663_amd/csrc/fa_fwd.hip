@@ -61,6 +61,7 @@ struct FaParams {
     int H, Nq, Nk;
     int q_rows;     // rows between consecutive heads of q, o, lse in memory (>= Nq: the call may cover a row range)
     int kv_rows;    // same for k, v (>= Nk)
+    int off;        // causal / window diagonal: row i of this launch sits on key i + off
     int nqt;        // query tiles per (b,h)
     int nwork;      // B*H*nqt
     int per_xcd;    // ceil(nwork / 8)
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     const int qt = (CAUSAL || GENMASK) ? (p.nqt - 1 - wi % p.nqt) : (wi % p.nqt);
 
     const int Nq = p.Nq, Nk = p.Nk;
-    const int off = Nk - Nq;
+    const int off = p.off;                        // key on the diagonal of query row 0 (Nk - Nq for a whole-q launch)
     int q_wave = qt * BM + wq * 32;               // first query row of this wave
     int last_row_wg = min(qt * BM + BM - 1, Nq - 1);   // last query row of the workgroup
     if (WIDE && CAUSAL && p.fold) {
@@ -782,6 +783,166 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     }
 }
 
+// ---- output projection (section 4.2: the Linear that follows the attention, computed block of rows by
+// block of rows right after it).  y[b, s, n] = sum_{h, d} o[b, h, s, d] * w[h*D + d, n] for the rows
+// s0 <= s < s0 + rows of every batch entry: a GEMM whose A operand is read straight out of the attention
+// output layout [B, H, Nq, D] (the heads are never copied side by side), fp32 accumulation, fp32 result.
+//
+// Workgroup tile 128 tokens x 256 outputs, K step 64, 8 waves as 2 (tokens) x 4 (outputs), wave tile 64 x 64
+// = 2 x 2 blocks of v_mfma_f32_32x32x16.  Both operand tiles go from global memory straight into LDS
+// (double-buffered, one k-tile ahead) with the bank swizzles of the attention kernel's K and V tiles: the o
+// tile (row-major, 128 B rows, k contiguous) is read with ds_read_b128 as the A operand; the w tile (row =
+// k, 512 B rows, n contiguous) is read with the transposing ds_read_b64_tr_b16 as the B operand.
+struct LinParams {
+    const uint16_t *o, *w;
+    float *y;
+    int H, q_rows, N;      // heads, rows between consecutive heads of o, outputs per token
+    int s0, rows;          // the block of rows
+    int mt_per_b;          // 128-row tiles per batch entry
+    int n_tiles;           // 256-wide tiles of N
+    int ntile_total, per_xcd;
+};
+
+template <int DT, int D>
+__global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
+    constexpr int BM = 128, BNO = 256, BK = 64;
+    constexpr int A_TILE = BM * BK * 2;           // 16 KiB
+    constexpr int W_TILE = BK * BNO * 2;          // 32 KiB
+    constexpr int STAGE = A_TILE + W_TILE;
+    constexpr int NST = 3;                        // tile buffers: loads run two k-tiles ahead (144 KiB)
+    __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    // workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of the tile list,
+    // ordered output-tile-major, so the workgroups sharing an L2 use the same few column slices of w
+    const int wi = (blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
+    if (wi >= p.ntile_total) return;
+    const int m_tiles = p.ntile_total / p.n_tiles;
+    const int nt = wi / m_tiles, mt = wi % m_tiles;
+    const int b = mt / p.mt_per_b;
+    const int r0 = (mt % p.mt_per_b) * BM;        // first row of the tile within the block
+    const int n0 = nt * BNO;
+    const int KT = p.H * D / BK;                  // k-tiles
+
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, smem));
+
+    // ---- loads.  o tile: instruction i (1 KiB) fills rows 8i..8i+7; this wave issues i = wave and wave + 8.
+    // The lane that owns LDS slot (row r, chunk c') fetches global chunk c' ^ ((r >> 1) & 7).  Rows past the
+    // end of the block are clamped to its last row (computed, never stored).
+    const int a_r = lane >> 3, a_c = lane & 7;
+    unsigned a_voff[2];
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        const int r = (wave + 8 * n) * 8 + a_r;
+        const int s = p.s0 + min(r0 + r, p.rows - 1);
+        a_voff[n] = (unsigned)(s * (D * 2) + ((a_c ^ ((r >> 1) & 7)) << 4));
+    }
+    // w tile: instruction i fills k-rows 2i, 2i+1 (512 B each); this wave issues i = wave + 8n, n = 0..3.
+    // The lane that owns slot (row r, byte b') fetches global byte b' ^ ((r & 3) << 6).
+    const int w_r = lane >> 5;
+    unsigned w_voff[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int r = (wave + 8 * n) * 2 + w_r;
+        w_voff[n] = (unsigned)(r * (p.N * 2) + (((lane & 31) << 4) ^ ((r & 3) << 6)));
+    }
+    const unsigned char *ob = (const unsigned char *)p.o;
+    const unsigned char *wb = (const unsigned char *)p.w + (size_t)n0 * 2;
+    auto load_tiles = [&](int kt, int st) __attribute__((always_inline)) {
+        const int k0 = kt * BK;
+        const int hh = k0 / D, d0 = k0 % D;
+        const unsigned char *ag = ob + ((size_t)(b * p.H + hh) * p.q_rows * D + d0) * 2;
+        const unsigned char *wg = wb + (size_t)k0 * p.N * 2;
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+            dma16_to_lds<0>(uniform_ptr(ag), a_voff[n], lds_base + st * STAGE + (wave + 8 * n) * 1024);
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+            dma16_to_lds<0>(uniform_ptr(wg), w_voff[n], lds_base + st * STAGE + A_TILE + (wave + 8 * n) * 1024);
+    };
+
+    // ---- operand fragments
+    auto a_frag = [&](const unsigned char *as, int mb, int ks) __attribute__((always_inline)) -> s16x8 {
+        return *(const s16x8 *)(as + k_lds_off<64>(wm * 64 + mb * 32 + l32, 2 * ks + h));
+    };
+    // k-slot (h, v) of 16-step ks is k = 16 ks + 8 h + v: two transposing reads of 4 k-rows x 16 outputs
+    const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
+    auto w_frag = [&](const unsigned char *ws, int ks, int nb) __attribute__((always_inline)) -> s16x8 {
+        const int row = 16 * ks + 8 * h + vi;
+        const int bcol = (wn * 64 + nb * 32) * 2 + g2 * 32 + vc * 8;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ws + row * 512 + (bcol ^ ((row & 3) << 6))));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ws + (row + 4) * 512 + (bcol ^ (((row + 4) & 3) << 6))));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = (f32x16)(0.f);
+
+    // k-tile kt lives in buffer kt % 3.  Iteration kt issues the loads of tile kt + 2 (into the buffer tile
+    // kt - 1 used: every wave has passed the barrier that ended iteration kt - 1), works on tile kt, then waits
+    // until its own share of tile kt + 1 has landed (loads complete in order: all but the newest six) and
+    // meets the other waves.
+    load_tiles(0, 0);
+    if (KT > 1) load_tiles(1, 1);
+    if (KT > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 6);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    int st = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 2 < KT;
+        if (more) load_tiles(kt + 2, st >= 1 ? st - 1 : 2);
+        const unsigned char *as = smem + st * STAGE;
+        const unsigned char *ws = as + A_TILE;
+        s16x8 af[2][2], wf[2][2];          // [ks parity][block]
+        af[0][0] = a_frag(as, 0, 0);
+        af[0][1] = a_frag(as, 1, 0);
+        wf[0][0] = w_frag(ws, 0, 0);
+        wf[0][1] = w_frag(ws, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < 4) {
+                af[nxt][0] = a_frag(as, 0, ks + 1);
+                af[nxt][1] = a_frag(as, 1, ks + 1);
+                wf[nxt][0] = w_frag(ws, ks + 1, 0);
+                wf[nxt][1] = w_frag(ws, ks + 1, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32<DT>(af[cur][mb], wf[cur][nb], acc[mb][nb]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) __builtin_amdgcn_s_waitcnt(0x0F70 | 6);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        st = st == 2 ? 0 : st + 1;
+    }
+
+    // ---- store: register r of block (mb, nb) is token row 8 (r/4) + 4 h + r%4, output column l32
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = r0 + wm * 64 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            if (row < p.rows) {
+                float *yp = p.y + ((size_t)b * p.q_rows + p.s0 + row) * p.N + n0 + wn * 64 + l32;
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) yp[nb * 32] = acc[mb][nb][r];
+            }
+        }
+}
+
 // Merge of the split-KV partial results (the same merge the split mode does between its two
 // wave groups): with M = max_s m_s, L = sum_s l_s 2^(m_s - M), the row is
 // o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
@@ -918,6 +1079,38 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
     return (int)n;
 }
 
+// the 16 plain instantiations: (split | wide) x dtype x head dimension x causal
+hipError_t launch_attention(const FaParams &p, int mode, int D, int causal, int dtype, int grid, hipStream_t st) {
+    hipError_t e;
+    const int key = ((mode != FA_MODE_SPLIT) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
+    switch (key) {
+        case 0: e = launch<0, 64, false, false>(p, grid, st); break;
+        case 1: e = launch<0, 64, true, false>(p, grid, st); break;
+        case 2: e = launch<0, 128, false, false>(p, grid, st); break;
+        case 3: e = launch<0, 128, true, false>(p, grid, st); break;
+        case 4: e = launch<1, 64, false, false>(p, grid, st); break;
+        case 5: e = launch<1, 64, true, false>(p, grid, st); break;
+        case 6: e = launch<1, 128, false, false>(p, grid, st); break;
+        case 7: e = launch<1, 128, true, false>(p, grid, st); break;
+        case 8: e = launch<0, 64, false, true>(p, grid, st); break;
+        case 9: e = launch<0, 64, true, true>(p, grid, st); break;
+        case 10: e = launch<0, 128, false, true>(p, grid, st); break;
+        case 11: e = launch<0, 128, true, true>(p, grid, st); break;
+        case 12: e = launch<1, 64, false, true>(p, grid, st); break;
+        case 13: e = launch<1, 64, true, true>(p, grid, st); break;
+        case 14: e = launch<1, 128, false, true>(p, grid, st); break;
+        case 15: e = launch<1, 128, true, true>(p, grid, st); break;
+        default: e = hipErrorInvalidValue; break;
+    }
+    return e;
+}
+
+template <int DT, int D>
+hipError_t launch_linear(const LinParams &p, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_linear_kernel<DT, D>), dim3(p.per_xcd * 8), dim3(512), 0, stream, p);
+    return hipGetLastError();
+}
+
 // The parameter block every entry point starts from: one launch over the whole of q (no row range,
 // no split, no descriptor mask).
 FaParams base_params(const void *q, const void *k, const void *v, void *o, float *lse, int H, int Nq, int Nk,
@@ -933,6 +1126,7 @@ FaParams base_params(const void *q, const void *k, const void *v, void *o, float
     p.Nk = Nk;
     p.q_rows = Nq;
     p.kv_rows = Nk;
+    p.off = Nk - Nq;
     p.nqt = (int)nqt;
     p.nwork = (int)nwork;
     p.per_xcd = (int)((nwork + 7) / 8);
@@ -1009,27 +1203,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
-    hipError_t e;
-    const int key = ((mode != FA_MODE_SPLIT) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
-    switch (key) {
-        case 0: e = launch<0, 64, false, false>(p, grid, st); break;
-        case 1: e = launch<0, 64, true, false>(p, grid, st); break;
-        case 2: e = launch<0, 128, false, false>(p, grid, st); break;
-        case 3: e = launch<0, 128, true, false>(p, grid, st); break;
-        case 4: e = launch<1, 64, false, false>(p, grid, st); break;
-        case 5: e = launch<1, 64, true, false>(p, grid, st); break;
-        case 6: e = launch<1, 128, false, false>(p, grid, st); break;
-        case 7: e = launch<1, 128, true, false>(p, grid, st); break;
-        case 8: e = launch<0, 64, false, true>(p, grid, st); break;
-        case 9: e = launch<0, 64, true, true>(p, grid, st); break;
-        case 10: e = launch<0, 128, false, true>(p, grid, st); break;
-        case 11: e = launch<0, 128, true, true>(p, grid, st); break;
-        case 12: e = launch<1, 64, false, true>(p, grid, st); break;
-        case 13: e = launch<1, 64, true, true>(p, grid, st); break;
-        case 14: e = launch<1, 128, false, true>(p, grid, st); break;
-        case 15: e = launch<1, 128, true, true>(p, grid, st); break;
-        default: return FA_ERR_SHAPE;
-    }
+    const hipError_t e = launch_attention(p, mode, D, causal, dtype, grid, st);
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return FA_ERR_LAUNCH;
@@ -1131,6 +1305,86 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return FA_ERR_LAUNCH;
+    }
+    return FA_OK;
+}
+
+int fa_attn_linear_block(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y,
+                         int B, int H, int Nq, int Nk, int D, int N, float scale, int causal, int dtype,
+                         int row_first, int row_count, void *stream) {
+    if (!q || !k || !v || !w || !o || !lse || !y) return FA_ERR_NULL;
+    const int rc = check_shape(B, H, Nq, Nk, D, dtype);
+    if (rc != FA_OK) return rc;
+    if (N <= 0 || N % 256 != 0 || (long long)N * H * D * 2 > 0x7fffffffLL) return FA_ERR_SHAPE;
+    if ((long long)Nq * D * 2 > 0x7fffffffLL) return FA_ERR_SHAPE;          // 32-bit offsets inside one head of o
+    if (row_first < 0 || row_count <= 0 || (long long)row_first + row_count > Nq) return FA_ERR_SHAPE;
+    if (!isfinite(scale)) return FA_ERR_SCALE;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)w) & 15) return FA_ERR_ALIGN;
+    if (((uintptr_t)lse | (uintptr_t)y) & 3) return FA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+
+    // 1. attention of the block's rows, every head: a launch over row_count rows whose diagonal is shifted
+    //    by row_first; q, o, lse keep the full tensors' head pitch
+    {
+        const int mode = choose_mode(B, H, row_count, causal);
+        const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
+        const long long nqt = ((long long)row_count + BM - 1) / BM;
+        const long long nwork = (long long)B * H * nqt;
+        FaParams p = base_params((const uint16_t *)q + (size_t)row_first * D, k, v, (uint16_t *)o + (size_t)row_first * D,
+                                 lse + row_first, H, row_count, Nk, nqt, nwork, scale);
+        p.q_rows = Nq;
+        p.off = Nk - Nq + row_first;
+        p.fold = mode == FA_MODE_WIDE_FOLD;
+        const hipError_t e = launch_attention(p, mode, D, causal, dtype, p.per_xcd * 8, st);
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+    }
+    // 2. the block's rows of y = (heads side by side) x w
+    {
+        LinParams lp;
+        lp.o = (const uint16_t *)o;
+        lp.w = (const uint16_t *)w;
+        lp.y = y;
+        lp.H = H;
+        lp.q_rows = Nq;
+        lp.N = N;
+        lp.s0 = row_first;
+        lp.rows = row_count;
+        lp.mt_per_b = (row_count + 127) / 128;
+        lp.n_tiles = N / 256;
+        const long long tiles = (long long)B * lp.mt_per_b * lp.n_tiles;
+        if (tiles > 0x7ffffff0LL) return FA_ERR_SHAPE;
+        lp.ntile_total = (int)tiles;
+        lp.per_xcd = (int)((tiles + 7) / 8);
+        hipError_t e;
+        switch ((dtype << 1) | (D == 128)) {
+            case 0: e = launch_linear<0, 64>(lp, st); break;
+            case 1: e = launch_linear<0, 128>(lp, st); break;
+            case 2: e = launch_linear<1, 64>(lp, st); break;
+            default: e = launch_linear<1, 128>(lp, st); break;
+        }
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+    }
+    return FA_OK;
+}
+
+int fa_attn_linear(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y, int B,
+                   int H, int Nq, int Nk, int D, int N, float scale, int causal, int dtype, int rows_per_block,
+                   void *stream) {
+    if (rows_per_block <= 0 || rows_per_block >= Nq)
+        return fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, 0, Nq, stream);
+    // the first block is half size (section 4.2: nothing overlaps with the first block's computation)
+    int first = rows_per_block / 2 > 0 ? rows_per_block / 2 : rows_per_block;
+    for (int r = 0; r < Nq;) {
+        const int n = r == 0 ? first : (Nq - r < rows_per_block ? Nq - r : rows_per_block);
+        const int rc = fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, r, n, stream);
+        if (rc != FA_OK) return rc;
+        r += n;
     }
     return FA_OK;
 }

@@ -105,6 +105,14 @@ DECODE = Config("DEC", 6, 2, 32, 1, 32768, 128, BF16, True)
 SLIDING = Config("SWA", 7, 2, 32, 16384, 16384, 128, BF16, True, 1.0, 4096)
 
 
+# Attention followed by the output projection, block of rows by block of rows (section 4.2): one sequence of
+# 8192 tokens at the same head layout, a 4096 x 4096 projection matrix drawn as N(0,1)/sqrt(4096), blocks of 2048
+# rows.  Not one of the five benchmark configurations.
+PROJECTION = Config("LIN", 8, 1, 32, 8192, 8192, 128, BF16, True)
+PROJECTION_N = 4096
+PROJECTION_ROWS_PER_BLOCK = 2048
+
+
 def normal_bits(shape, seed: int, dtype: int, mult: float = 1.0) -> np.ndarray:
     """i.i.d. N(0,1)*mult drawn in fp32 from PCG64(seed), rounded once to the storage format."""
     rng = np.random.Generator(np.random.PCG64(seed))

@@ -72,6 +72,31 @@ def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, p
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy()
 
 
+def run_attn_linear(q_bits, k_bits, v_bits, w_bits, scale, causal, dtype, blocks=None, rows_per_block=0):
+    """fa_attn_linear (blocks=None) or one fa_attn_linear_block call per (row_first, row_count) in ``blocks``.
+    Outputs are poisoned first.  Returns (o_bits, lse, y) as numpy."""
+    import torch
+    assert torch.cuda.is_available()
+    B, H, Nq, D = q_bits.shape
+    Nk = k_bits.shape[2]
+    N = w_bits.shape[1]
+    dev = torch.device("cuda:0")
+    tq, tk, tv, tw = (torch.from_numpy(a.view(np.int16)).to(dev) for a in (q_bits, k_bits, v_bits, w_bits))
+    to = torch.full((B, H, Nq, D), 0x7E00 if dtype == I.F16 else 0x7FC0, dtype=torch.int16, device=dev)
+    tl = torch.full((B, H, Nq), float("nan"), dtype=torch.float32, device=dev)
+    ty = torch.full((B, Nq, N), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    if blocks is None:
+        fa.fa_attn_linear(tq, tk, tv, tw, to, tl, ty, B, H, Nq, Nk, D, N, scale, int(causal), dtype, rows_per_block,
+                          stream)
+    else:
+        for r0, n in blocks:
+            fa.fa_attn_linear_block(tq, tk, tv, tw, to, tl, ty, B, H, Nq, Nk, D, N, scale, int(causal), dtype, r0, n,
+                                    stream)
+    torch.cuda.synchronize()
+    return to.cpu().numpy().view(np.uint16), tl.cpu().numpy(), ty.cpu().numpy()
+
+
 def bf16_half_ulp(x):
     """Half a unit in the last place of bfloat16 (8 significant bits) at magnitude |x|."""
     ax = np.maximum(np.abs(x), 2.0 ** -126)

@@ -103,6 +103,27 @@ def test_splitkv_plan(lib):
     assert fa.load().fa_fwd_splitkv_plan(1, 1, 8, 8, 64, 0, 0, 0, None) == fa.FA_ERR_NULL
 
 
+LIN_GOOD = dict(q=0x1000, k=0x2000, v=0x3000, w=0x7000, o=0x4000, lse=0x5000, y=0x8000, B=1, H=2, Nq=300, Nk=300, D=64,
+                N=256, scale=0.125, causal=1, dtype=0, row_first=0, row_count=300)
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(w=0), fa.FA_ERR_NULL), (dict(y=0), fa.FA_ERR_NULL), (dict(o=0), fa.FA_ERR_NULL),
+    (dict(N=0), fa.FA_ERR_SHAPE), (dict(N=200), fa.FA_ERR_SHAPE), (dict(N=257), fa.FA_ERR_SHAPE),
+    (dict(row_first=-1), fa.FA_ERR_SHAPE), (dict(row_count=0), fa.FA_ERR_SHAPE),
+    (dict(row_first=200, row_count=101), fa.FA_ERR_SHAPE), (dict(D=100), fa.FA_ERR_HEADDIM),
+    (dict(dtype=2), fa.FA_ERR_DTYPE), (dict(scale=float("nan")), fa.FA_ERR_SCALE),
+    (dict(w=0x7008), fa.FA_ERR_ALIGN), (dict(y=0x8002), fa.FA_ERR_ALIGN),
+])
+def test_attn_linear_argument_errors_come_back_before_any_launch(lib, change, code):
+    args = dict(LIN_GOOD)
+    args.update(change)
+    assert fa.fa_attn_linear_block_raw(**args) == code
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_attn_linear_block(**args)
+    assert e.value.code == code
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(fa, "_lib", None)
     monkeypatch.setattr(fa, "LIB_PATH", str(tmp_path / "libfa.so"))
@@ -215,8 +236,8 @@ def test_build_report_shows_register_only_kernels():
     from paper_2410_16663_amd import build
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
-    # combine: 2 dtypes x 2 head dims
-    assert len(build.last_report) == 24 + 4 + 4
+    # combine: 2 dtypes x 2 head dims; output projection: 2 dtypes x 2 head dims
+    assert len(build.last_report) == 24 + 4 + 4 + 4
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

@@ -1,0 +1,106 @@
+"""GPU parity of fa_attn_linear / fa_attn_linear_block (attention + output projection per block of rows,
+section 4.2) against the CPU fp64 oracle.
+
+o and lse: the tolerances of fa_fwd.  y = (heads side by side) x w with w ~ N(0,1)/sqrt(H*D): the error of y is
+a sum of H*D errors of o weighted by entries of size 1/sqrt(H*D), i.e. of the size of one error of o: the same
+bounds apply, max-abs 1e-2 and mean-abs 1e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2410_16663_amd import inputs as I
+from gpu_util import check_against_oracle, run_attn_linear, run_fa_fwd
+
+pytestmark = pytest.mark.gpu
+
+Y_MAX_ABS = 1e-2
+Y_MEAN_ABS = 1e-3
+
+
+def rand_bits(rng, shape, dtype, mult=1.0):
+    return I.f32_to_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(mult), dtype)
+
+
+def make(rng, B, H, Nq, Nk, D, N, dtype):
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    w = rand_bits(rng, (H * D, N), dtype, 1.0 / math.sqrt(H * D))
+    return q, k, v, w
+
+
+def check_y(y, y_ref, label):
+    assert np.isfinite(y).all(), f"{label}: non-finite or unwritten y"
+    err = np.abs(y.astype(np.float64) - y_ref)
+    assert err.max() <= Y_MAX_ABS, f"{label}: y max-abs {err.max():.3e}"
+    assert err.mean() <= Y_MEAN_ABS, f"{label}: y mean-abs {err.mean():.3e}"
+
+
+# B, H, Nq, Nk, D, N
+SHAPES = [(1, 2, 300, 300, 64, 256), (2, 3, 200, 333, 128, 512), (1, 4, 130, 130, 128, 256), (2, 2, 1, 500, 64, 256),
+          (1, 1, 257, 129, 128, 768)]
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("rows_per_block", [0, 128, 100])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_whole_problem_in_blocks(oracle, shape, rows_per_block, causal, dtype):
+    B, H, Nq, Nk, D, N = shape
+    print(f"case attn_linear shape={shape} rpb={rows_per_block} causal={causal} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, causal, dtype)) % (2**32))
+    q, k, v, w = make(rng, B, H, Nq, Nk, D, N, dtype)
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
+    y_ref = oracle.attention_linear(q, k, v, w, scale, causal, dtype)
+    o, lse, y = run_attn_linear(q, k, v, w, scale, causal, dtype, rows_per_block=rows_per_block)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} rpb={rows_per_block}")
+    check_y(y, y_ref, f"{shape} rpb={rows_per_block}")
+
+
+def test_blocks_are_independent_and_touch_only_their_rows(oracle):
+    """Arbitrary blocks, out of order, leaving a gap: the gap's rows of o, lse, y stay as they were."""
+    print("case attn_linear arbitrary blocks", flush=True)
+    rng = np.random.default_rng(601)
+    B, H, Nq, Nk, D, N = 2, 2, 400, 450, 128, 256
+    q, k, v, w = make(rng, B, H, Nq, Nk, D, N, I.F16)
+    scale = 0.09
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, I.F16)
+    y_ref = oracle.attention_linear(q, k, v, w, scale, True, I.F16)
+    o, lse, y = run_attn_linear(q, k, v, w, scale, True, I.F16, blocks=[(300, 100), (0, 70), (70, 131)])
+    done = np.zeros(Nq, dtype=bool)
+    done[0:201] = True
+    done[300:400] = True
+    check_against_oracle(o[:, :, done], lse[:, :, done], o_ref[:, :, done], lse_ref[:, :, done], I.F16, "blocks")
+    check_y(y[:, done], y_ref[:, done], "blocks")
+    assert np.isnan(y[:, ~done]).all() and np.isnan(lse[:, :, ~done]).all() and (o[:, :, ~done] == 0x7E00).all()
+
+
+def test_one_block_gives_fa_fwd_bit_for_bit_and_exact_projections():
+    """The whole problem as one block runs the same attention launch as fa_fwd; with w = identity columns the
+    projection returns o itself (products with 1 and 0, fp32 sums of one term)."""
+    print("case attn_linear exact", flush=True)
+    rng = np.random.default_rng(602)
+    for dtype, D in ((I.F16, 64), (I.BF16, 128)):
+        B, H, Nq, Nk = 1, 256 // D, 333, 333
+        q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+        w = I.f32_to_bits(np.eye(H * D, 256, dtype=np.float32), dtype)
+        o0, lse0 = run_fa_fwd(q, k, v, 0.11, True, dtype)
+        o, lse, y = run_attn_linear(q, k, v, w, 0.11, True, dtype)
+        assert np.array_equal(o, o0) and np.array_equal(lse, lse0)
+        side_by_side = I.bits_to_f64(o, dtype).transpose(0, 2, 1, 3).reshape(B, Nq, H * D)
+        assert np.array_equal(y.astype(np.float64), side_by_side)
+
+
+def test_llama7b_layer_shape_on_sampled_tokens(oracle):
+    """The shape bench.py times: C2's attention (32 heads of 128) and a 4096 x 4096 projection, four blocks."""
+    cfg = I.CONFIGS["C2"]
+    print("case attn_linear C2 + 4096x4096 projection", flush=True)
+    q, k, v = I.make_qkv(cfg)
+    w = I.normal_bits((cfg.H * cfg.D, 4096), 2003, cfg.dtype, 1.0 / math.sqrt(cfg.H * cfg.D))
+    o, lse, y = run_attn_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows_per_block=512)
+    rows = np.array([0, 1, 127, 128, 255, 256, 300, 511, 512, 1000, 1023, 1024, 1500, 1535, 1536, 2047])
+    y_ref = oracle.attention_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows=rows)
+    check_y(y[0, rows], y_ref, "C2 projection sample")
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
+    check_against_oracle(o, lse, o_ref, lse_ref, cfg.dtype, "C2 in blocks")
