@@ -213,6 +213,30 @@ def projection_entry(I, torch, fa, steps, warmup):
                          "flops_per_call": fl_attn + fl_proj, "flops_attention": fl_attn, "flops_projection": fl_proj}}
 
 
+def cpu_decode_entry(I, np):
+    """The host-side decoding attention of the cooperative strategy (fa_cpu_decode) on one GPU's share of the
+    decoding workload's heads, timed on the machine's host cores; bytes = K and V read once."""
+    from paper_2410_16663_amd import cpu_binding as fc
+    c = I.DECODE
+    B, H = 1, 8
+    q = I.normal_bits((B, H, 1, c.D), c.seeds[0], c.dtype)
+    k = I.normal_bits((B, H, c.Nk, c.D), c.seeds[1], c.dtype)
+    v = I.normal_bits((B, H, c.Nk, c.D), c.seeds[2], c.dtype)
+    o = np.empty((B, H, 1, c.D), dtype=np.uint16)
+    lse = np.empty((B, H, 1), dtype=np.float32)
+    fc.fa_cpu_decode(q, k, v, o, lse, B, H, c.Nk, c.D, c.scale, c.dtype, 0)     # warm-up
+    reps = 10
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fc.fa_cpu_decode(q, k, v, o, lse, B, H, c.Nk, c.D, c.scale, c.dtype, 0)
+    ms = (time.perf_counter() - t0) * 1e3 / reps
+    kv_bytes = 2.0 * B * H * c.Nk * c.D * 2
+    return {"workload": f"B={B} H={H} Nq=1 Nk={c.Nk} D={c.D} bf16 (host memory)", "entry_point": "fa_cpu_decode",
+            "ms_per_call": round(ms, 4), "gb_per_s": round(kv_bytes / (ms * 1e-3) / 1e9, 2),
+            "threads": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "avx512": fc.fa_cpu_has_avx512(),
+            "bound": "host memory bandwidth", "bytes_per_call": kv_bytes}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -330,6 +354,7 @@ def main():
         extra["SWA"] = sliding_entry(I, torch, fa, 10, 2)
         torch.cuda.empty_cache()
         extra["LIN"] = projection_entry(I, torch, fa, 10, 2)
+        extra["CPU_DEC"] = cpu_decode_entry(I, np)
         out["other_workloads"] = extra
 
     print(json.dumps(out), flush=True)

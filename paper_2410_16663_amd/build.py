@@ -1,4 +1,5 @@
-"""Build the C-ABI HIP library (csrc/fa_fwd.hip -> libfa.so) for gfx950 with hipcc.
+"""Build the C-ABI HIP library (csrc/fa_fwd.hip -> libfa.so) for gfx950 with hipcc, and the host-side
+library of the CPU-GPU cooperative strategy (csrc/fa_cpu.c -> libfa_cpu.so) with gcc.
 
 hipcc cross-compiles without a GPU, so this runs on any machine with ROCm installed.
 """
@@ -82,5 +83,25 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+CPU_SRC = os.path.join(HERE, "csrc", "fa_cpu.c")
+CPU_HDR = os.path.join(os.path.dirname(HERE), "include", "fa_cpu.h")
+CPU_LIB = os.path.join(HERE, "libfa_cpu.so")
+
+
+def build_cpu(force: bool = True) -> str:
+    """Compile libfa_cpu.so (plain C + OpenMP; the AVX-512 loops are compiled for that target inside the file
+    and chosen at run time, so no -march flag here)."""
+    if not force and os.path.exists(CPU_LIB) and all(
+            os.path.getmtime(f) <= os.path.getmtime(CPU_LIB) for f in (CPU_SRC, CPU_HDR)):
+        return CPU_LIB
+    cmd = [os.environ.get("CC", "gcc"), "-O3", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", CPU_SRC, "-o",
+           CPU_LIB, "-lm"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gcc failed:\n{r.stdout}\n{r.stderr}")
+    return CPU_LIB
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_cpu(force=True))

@@ -1,0 +1,204 @@
+"""The host-side half of the CPU-GPU cooperative strategy (section 4.4, appendix C): the layer split and the
+decoding-step attention on the CPU, through the C ABI of include/fa_cpu.h.  No GPU needed.
+
+fa_cpu_decode is checked against the same fp64 oracle as the GPU kernels, with the same tolerances
+(O max-abs 1e-2, mean-abs 1e-3, LSE 1e-3) and, since it accumulates in fp32 without rounding the
+probabilities, a much tighter one as well: within one unit in the last place of the output format.
+"""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_16663_amd import cpu_binding as fc
+from paper_2410_16663_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2410_16663_amd import build
+    build.build_cpu(force=False)
+    return fc.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "fa_cpu.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(fc.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+# ---------------------------------------------------------------- layer split
+def test_plan_hand_example(lib):
+    # one GPU's 100 bytes, a quarter of 80 bytes of weights, 10 + 5 bytes of the rest: 65 bytes for 7-byte layers
+    assert fc.fa_coop_plan_bytes(100, 80, 10, 5, 7, 4, 12) == (9, 3)
+    assert fc.fa_coop_plan_bytes(100, 80, 10, 5, 7, 4, 5) == (5, 0)      # everything fits: no layer on the CPU
+    assert fc.fa_coop_plan_bytes(100, 80, 10, 5, 65, 4, 12) == (1, 11)   # exactly one layer
+    assert fc.fa_coop_plan_bytes(100, 80, 10, 5, 65.01, 4, 12) == (0, 12)
+    assert fc.fa_coop_plan_bytes(30, 80, 10, 5, 7, 4, 12) == (0, 12)     # weights alone do not fit: all on the CPU
+
+
+def first_principles_bytes(n, L, H1, H2, V, B, S, O):
+    """Appendix C's memory terms counted from the tensors they stand for (2 bytes per FP16 element)."""
+    per_layer_weights = 4 * (H1 * H1) + 2 * (H1 * H2)        # W_Q, W_K, W_V, W_O and W_1, W_2
+    m_w = L * per_layer_weights * 2
+    m_kv = 2 * (B * (S + O) * H1) * 2 / n                    # K and V of prompt + generated tokens, over n GPUs
+    m_mid = 3 * (B * S * H1) * 2 / n                         # Q, K, V of the prompt
+    m_vocab = V * H1                                         # as the appendix prints it
+    return m_w, m_mid, m_vocab, m_kv
+
+
+@pytest.mark.parametrize("model", [
+    # n, L, H1, H2, V  (PanGu-38B, LLaMA2-7B, LLaMA2-70B shapes of the paper's model table; V chosen)
+    (8, 40, 5120, 20480, 40000), (1, 32, 4096, 11008, 32000), (8, 80, 8192, 28672, 32000),
+])
+@pytest.mark.parametrize("m_gpu", [16e9, 32e9, 288e9])
+@pytest.mark.parametrize("B,S,O", [(1, 16384, 50), (1, 262144, 50), (8, 2048, 512), (64, 131072, 1)])
+def test_closed_form_equals_general_form_on_first_principles_bytes(lib, model, m_gpu, B, S, O):
+    n, L, H1, H2, V = model
+    m_w, m_mid, m_vocab, m_kv = first_principles_bytes(n, L, H1, H2, V, B, S, O)
+    general = fc.fa_coop_plan_bytes(m_gpu, m_w, m_mid, m_vocab, m_kv, n, L)
+    closed = fc.fa_coop_plan_fp16(m_gpu, n, L, H1, H2, V, B, S, O)
+    assert general == closed
+    assert sum(closed) == L and 0 <= closed[0] <= L
+    # independent arithmetic in exact integers
+    num = int(n * m_gpu) - L * (8 * H1 * H1 + 4 * H1 * H2) - 6 * B * S * H1 - n * V * H1
+    want = min(max(num // (4 * B * H1 * (S + O)), 0), L)
+    assert closed[0] == want
+
+
+def test_plan_is_monotone(lib):
+    n, L, H1, H2, V = 8, 40, 5120, 20480, 40000
+    prev = -1
+    for m_gpu in np.linspace(4e9, 64e9, 40):
+        l_gpu, l_cpu = fc.fa_coop_plan_fp16(m_gpu, n, L, H1, H2, V, 1, 262144, 50)
+        assert l_gpu >= prev and l_gpu + l_cpu == L
+        prev = l_gpu
+    prev = L + 1
+    for S in (1024, 8192, 65536, 262144, 1 << 20, 1 << 22):
+        l_gpu, _ = fc.fa_coop_plan_fp16(16e9, n, L, H1, H2, V, 1, S, 50)
+        assert l_gpu <= prev
+        prev = l_gpu
+    assert fc.fa_coop_plan_fp16(16e9, n, L, H1, H2, V, 1, 1024, 50) == (L, 0)      # short prompts need no CPU layer
+    assert fc.fa_coop_plan_fp16(16e9, n, L, H1, H2, V, 1, 1 << 22, 50)[1] > 0      # very long ones do
+
+
+def test_plan_argument_errors(lib):
+    for args in ((100, 80, 10, 5, 0, 4, 12), (100, 80, 10, 5, 7, 0, 12), (100, 80, 10, 5, 7, 4, 0),
+                 (100, -1, 10, 5, 7, 4, 12), (float("nan"), 80, 10, 5, 7, 4, 12)):
+        with pytest.raises(fc.FaCpuError) as e:
+            fc.fa_coop_plan_bytes(*args)
+        assert e.value.code == fc.FA_CPU_ERR_SHAPE
+    with pytest.raises(fc.FaCpuError):
+        fc.fa_coop_plan_fp16(16e9, 8, 40, 0, 20480, 40000, 1, 1024, 50)
+    assert lib.fa_coop_plan_bytes(100.0, 80.0, 10.0, 5.0, 7.0, 4, 12, None, None) == fc.FA_CPU_ERR_NULL
+
+
+# ---------------------------------------------------------------- decoding-step attention on the CPU
+def rand_bits(rng, shape, dtype, mult=1.0):
+    return I.f32_to_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(mult), dtype)
+
+
+def ulp(x, dtype):
+    bits = 10 if dtype == I.F16 else 7
+    ax = np.maximum(np.abs(x), 2.0 ** (-14 if dtype == I.F16 else -126))
+    return 2.0 ** (np.floor(np.log2(ax)) - bits)
+
+
+def run_cpu_decode(q, k, v, scale, dtype, nthreads=0):
+    B, H, _, D = q.shape
+    Nk = k.shape[2]
+    o = np.full((B, H, 1, D), 0x7E00 if dtype == I.F16 else 0x7FC0, dtype=np.uint16)
+    lse = np.full((B, H, 1), np.nan, dtype=np.float32)
+    fc.fa_cpu_decode(np.ascontiguousarray(q), np.ascontiguousarray(k), np.ascontiguousarray(v), o, lse, B, H, Nk, D,
+                     scale, dtype, nthreads)
+    return o, lse
+
+
+@pytest.fixture(params=["avx512", "scalar"])
+def path(request, monkeypatch, lib):
+    if request.param == "scalar":
+        monkeypatch.setenv("FA_CPU_FORCE_SCALAR", "1")
+        assert not fc.fa_cpu_has_avx512()
+    elif not fc.fa_cpu_has_avx512():
+        pytest.skip("this CPU has no AVX-512")
+    return request.param
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("shape", [(1, 2, 1, 64), (2, 3, 1000, 128), (1, 4, 20000, 128), (1, 1, 37, 16), (3, 2, 515, 256),
+                                   (1, 1, 4097, 64)])
+def test_cpu_decode_against_the_oracle(oracle, path, shape, dtype):
+    B, H, Nk, D = shape
+    rng = np.random.default_rng(hash((shape, dtype)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (1, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, dtype)      # decode: causal = the whole cache
+    for nthreads in (1, 4):
+        o, lse = run_cpu_decode(q, k, v, scale, dtype, nthreads)
+        of = I.bits_to_f64(o, dtype)
+        err = np.abs(of - o_ref)
+        assert err.max() <= 1e-2 and err.mean() <= 1e-3
+        assert (err <= ulp(o_ref, dtype) + 1e-6).all(), f"{path} {shape}: {err.max():.3e}"
+        assert np.abs(lse - lse_ref).max() <= 1e-3
+        assert np.abs(lse - lse_ref).max() <= 2e-5 * max(1.0, np.abs(lse_ref).max())
+
+
+@pytest.mark.parametrize("scale", [-0.4, 0.0, 3.0])
+def test_cpu_decode_scales_and_large_logits(oracle, path, scale):
+    rng = np.random.default_rng(701)
+    q, k, v = (rand_bits(rng, (2, 2, n, 64), I.F16, 2.0) for n in (1, 3000, 3000))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, False, I.F16)
+    o, lse = run_cpu_decode(q, k, v, scale, I.F16, 3)
+    err = np.abs(I.bits_to_f64(o, I.F16) - o_ref)
+    assert (err <= ulp(o_ref, I.F16) + 1e-6).all()
+    assert np.abs(lse - lse_ref).max() <= 2e-4
+
+
+def test_cpu_decode_single_key_returns_every_value_bit_pattern(path):
+    """Nk = 1: o = v[0] exactly -- exercises the 16-bit decoding and the rounding back for every finite pattern."""
+    for dtype in (I.F16, I.BF16):
+        exp_mask = 0x7C00 if dtype == I.F16 else 0x7F80
+        pats = np.array([b for b in range(65536) if (b & exp_mask) != exp_mask], dtype=np.uint16)
+        D = 256
+        pats = pats[: len(pats) // D * D].reshape(-1, 1, 1, D)       # [B, 1, 1, D]
+        B = pats.shape[0]
+        q = np.zeros((B, 1, 1, D), dtype=np.uint16)
+        o, lse = run_cpu_decode(q, np.zeros_like(pats), pats, 1.0, dtype, 2)
+        same = o == pats
+        assert same[pats != 0x8000].all()                         # every pattern comes back bit for bit ...
+        assert (I.bits_to_f64(o, dtype) == I.bits_to_f64(pats, dtype)).all()   # ... and -0 as a zero (0 + 1 * -0 = +0)
+        assert (lse == 0).all()
+
+
+def test_cpu_decode_rounds_to_nearest_even(path):
+    """Two keys with equal logits: o = the mean of two values, chosen to fall exactly between two representable
+    numbers (ties to even) and just off the tie."""
+    for dtype, one_ulp in ((I.F16, 2.0 ** -10), (I.BF16, 2.0 ** -7)):
+        D = 16
+        a = np.array([1.0, 1.0 + one_ulp, 1.0 + 2 * one_ulp, 2.0 - one_ulp] * 4, dtype=np.float64)
+        b = a + one_ulp            # mean = a + ulp/2: a tie
+        v = np.stack([a, b])[None, None]                                     # [1,1,2,D]
+        vb = I.f32_to_bits(v.astype(np.float32), dtype)
+        assert np.array_equal(I.bits_to_f64(vb, dtype), v)                  # exactly representable
+        q = np.zeros((1, 1, 1, D), dtype=np.uint16)
+        o, _ = run_cpu_decode(q, np.zeros_like(vb), vb, 1.0, dtype, 1)
+        want = I.f32_to_bits(((a + b) / 2).astype(np.float32)[None, None, None], dtype)   # numpy: nearest even
+        assert np.array_equal(o, want)
+
+
+def test_cpu_decode_argument_errors(lib):
+    good = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, Nk=8, D=64, scale=0.1, dtype=0)
+    for change, code in ((dict(q=0), fc.FA_CPU_ERR_NULL), (dict(lse=0), fc.FA_CPU_ERR_NULL),
+                         (dict(B=0), fc.FA_CPU_ERR_SHAPE), (dict(Nk=0), fc.FA_CPU_ERR_SHAPE),
+                         (dict(D=24), fc.FA_CPU_ERR_HEADDIM), (dict(D=512), fc.FA_CPU_ERR_HEADDIM),
+                         (dict(dtype=2), fc.FA_CPU_ERR_DTYPE), (dict(scale=float("inf")), fc.FA_CPU_ERR_SCALE)):
+        args = dict(good)
+        args.update(change)
+        assert fc.fa_cpu_decode_raw(**args) == code
