@@ -72,15 +72,16 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * skipped; appendix A: the work is split over the sequence as well as over batch and heads).
  * FA_MODE_SPLIT: a workgroup owns 128 query rows and its two wave groups take alternate
  * 64-key tiles; FA_MODE_WIDE: a workgroup owns 256 query rows and all its waves walk the same
- * tiles.  With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256, WIDE_FOLD when the problem is
- * causal with 256 < Nq <= 4096 and W < 384 (about one workgroup per compute unit), else WIDE; the environment variable FA_FWD_MODE=split|wide|fold
- * overrides the choice (for tests and tuning).
+ * tiles; FA_MODE_WIDE_FOLD (causal only): WIDE with each workgroup's eight 32-row blocks taken
+ * four from the cheap end of the sequence and four, mirrored, from the expensive end.
+ * With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256; for causal problems with
+ * Nq > 256: WIDE_FOLD when Nq <= 2048, W <= 1024 and the last round of 256 workgroups is at
+ * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); WIDE otherwise.
+ * The environment variable FA_FWD_MODE=split|wide|fold overrides the choice (tests, tuning).
  */
 #define FA_MODE_SPLIT 0
 #define FA_MODE_WIDE  1
-#define FA_MODE_WIDE_FOLD 2 /* WIDE, causal only: each workgroup's eight 32-row blocks are spread over the
-                               sequence (one from each eighth, alternating direction) so that all workgroups
-                               carry the same amount of triangular work */
+#define FA_MODE_WIDE_FOLD 2
 
 typedef struct fa_plan {
     int mode;                 /* FA_MODE_SPLIT, FA_MODE_WIDE or FA_MODE_WIDE_FOLD */

@@ -145,15 +145,19 @@ __host__ __device__ inline TileSeq tile_sequence(const MaskGeom &g, int R0, int 
     return {p_t, w_lo, p_t + (w_hi - w_lo + 1)};
 }
 
-// Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into
-// 32-row blocks; the blocks are taken in 8 rounds of G (= workgroups per head) consecutive
-// blocks, and workgroup g owns one block of every round -- block g of the even rounds, block
-// G-1-g of the odd ones -- so every workgroup gets the same mix of early (cheap) and late
-// (expensive) causal rows instead of 256 consecutive ones.  Wave w works on round 7-w (w < 4)
-// or w-4 (w >= 4): the two waves that share a SIMD (w and w+4) hold rounds r and 7-r.
+// Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into 8 G
+// blocks of 32 rows (G = workgroups per head); block i needs about i/2 + 1 key tiles.  Workgroup g
+// owns the four blocks 4g .. 4g+3 from the cheap end and their mirror images 8G-1-4g-j from the
+// expensive end, so every workgroup carries the same amount of triangular work.  Wave w < 4 takes
+// cheap block 4g + w, and wave w + 4 -- the wave it shares a SIMD with -- the mirror image of it.
+// All four SIMDs of a workgroup then hold the same kind of pair (one short walk, one long walk of
+// nearly equal lengths across the SIMDs): the waves meet at a barrier per tile, so an iteration costs
+// what its busiest SIMD costs, and with like pairs no SIMD is still running two waves after the
+// others have dropped to one.  (Dealing one block of every eighth of the sequence to each workgroup
+// balances the work just as well but mixes pairs of 4+32 ... 16+20 tiles in one workgroup: measured
+// 25% slower.)
 __host__ __device__ inline int fold_block(int G, int g, int w) {
-    const int r = w < 4 ? 7 - w : w - 4;
-    return r * G + ((r & 1) ? (G - 1 - g) : g);
+    return w < 4 ? 4 * g + w : 8 * G - 1 - 4 * g - (w - 4);
 }
 
 // The run of positions [first, first + count) of a workgroup's walk that a wave (row limits w) can
@@ -295,7 +299,14 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 #endif
     // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead.  Two for the compute-bound shapes (3 measured
     // slower); the split-KV shapes are bound by HBM latency x bandwidth and take a third
-    constexpr int NSTAGE = SPLITKV ? FA_SPLITKV_STAGES : 2;
+#ifndef FA_WIDE_STAGES
+#define FA_WIDE_STAGES 2
+#endif
+#ifndef FA_LOADS_FIRST
+#define FA_LOADS_FIRST 0
+#endif
+    constexpr int NSTAGE = SPLITKV ? FA_SPLITKV_STAGES : (WIDE ? FA_WIDE_STAGES : 2);
+    constexpr bool LOADS_FIRST = SPLITKV || FA_LOADS_FIRST;
     constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
     constexpr int NSETS = WIDE ? 1 : 2;           // split mode: one set per group
 
@@ -642,9 +653,9 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             // the loads go out between the two matrix clusters (measured 1% better than up front:
             // their LDS writes then land mostly during the softmax, when no wave reads LDS);
             // split-KV waits on HBM, not on LDS: there they go out first
-            if (SPLITKV && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
+            if (LOADS_FIRST && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
             qk_cluster(st_c);
-            if (!SPLITKV && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
+            if (!LOADS_FIRST && issued) { load_k(j + PD, ST_LOAD, std::false_type{}); load_v(j + PD, ST_LOAD, std::false_type{}); }
             softmax_cluster(j, std::true_type{});
             pv_cluster(st_c);
         } else if (issued) {
@@ -661,9 +672,9 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // (written for two buffers; with more the general loop does everything)
     auto interior = [&](auto st_c, int j) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;
+        if (LOADS_FIRST) { load_k(j + 1, ST ^ 1, std::true_type{}); load_v(j + 1, ST ^ 1, std::true_type{}); }
         qk_cluster(st_c);
-        load_k(j + 1, ST ^ 1, std::true_type{});
-        load_v(j + 1, ST ^ 1, std::true_type{});
+        if (!LOADS_FIRST) { load_k(j + 1, ST ^ 1, std::true_type{}); load_v(j + 1, ST ^ 1, std::true_type{}); }
         softmax_cluster(j, std::false_type{});
         pv_cluster(st_c);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -1017,22 +1028,31 @@ int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
     return FA_OK;
 }
 
-// FA_MODE_WIDE when there are at least as many 256-row workgroups as compute units (256), else
-// FA_MODE_SPLIT, which doubles the workgroup count and halves each one's chain of tiles; the
-// environment variable FA_FWD_MODE ("split" / "wide") overrides.
+// Work decomposition for a problem, W = B * H * ceil(Nq / 256) being the number of 256-row workgroups
+// (the chip has 256 compute units and a D = 128 workgroup fills one).  Measured on causal problems:
+//  * fewer workgroups than compute units: FA_MODE_SPLIT doubles their number and halves their chains;
+//  * causal, short sequences (Nq <= 2048), up to four rounds of workgroups that fill their last round
+//    to 85%: FA_MODE_WIDE_FOLD -- every workgroup carries the same triangular work, so whole rounds
+//    take equal time (7-17% faster than the others there; with a poorly filled last round it loses to
+//    the split mode, whose workgroups are half the size);
+//  * causal, longer sequences with few rounds (W < 640 up to Nq = 4096, W < 384 beyond): FA_MODE_SPLIT,
+//    whose shorter chains matter more than its extra K/V traffic (up to 29% faster than wide there);
+//  * otherwise FA_MODE_WIDE: with many rounds the heavy-first dynamic dispatch evens out the triangle.
+// The environment variable FA_FWD_MODE ("split" / "wide" / "fold") overrides.
 int choose_mode(int B, int H, int Nq, int causal) {
     const char *env = getenv("FA_FWD_MODE");
     if (env && !strcmp(env, "split")) return FA_MODE_SPLIT;
     if (env && !strcmp(env, "wide")) return FA_MODE_WIDE;
     if (env && !strcmp(env, "fold")) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
     const long long nqt = ((long long)Nq + 255) / 256;
-    const long long wide_work = (long long)B * H * nqt;
-    if (wide_work < 256) return FA_MODE_SPLIT;
-    // causal, more than one block per head and about one workgroup per compute unit: nothing
-    // evens out the triangular work but the folded order.  (With more workgroups the dynamic
-    // dispatch of heavy-first work does it better: folding makes every workgroup walk nearly
-    // all tiles with ever fewer busy waves; measured 25% slower at two workgroups per CU.)
-    if (causal && nqt >= 2 && wide_work < 384 && Nq <= 4096) return FA_MODE_WIDE_FOLD;
+    const long long W = (long long)B * H * nqt;
+    if (W < 256) return FA_MODE_SPLIT;
+    if (causal && nqt >= 2) {
+        const long long rounds = (W + 255) / 256;
+        const bool fills_last_round = rounds * 256 * 100 <= W * 115;
+        if (Nq <= 2048 && W <= 1024 && fills_last_round) return FA_MODE_WIDE_FOLD;
+        if (Nq <= 4096 ? W < 640 : W < 384) return FA_MODE_SPLIT;
+    }
     return FA_MODE_WIDE;
 }
 

@@ -159,12 +159,12 @@ def test_causal_plan_skips_the_tiles_above_the_diagonal(lib, monkeypatch, mode, 
 
 
 def folded_rows(G, g, Nq):
-    """Rows of workgroup g of G under the folded assignment: one 32-row block from each of the 8
-    rounds of G consecutive blocks, in alternating direction."""
+    """Rows of workgroup g of G under the folded assignment: of the head's 8 G blocks of 32 rows, the four
+    blocks 4g .. 4g+3 and their mirror images counted from the other end."""
     rows = []
-    for r in range(8):
-        blk = r * G + (G - 1 - g if r % 2 else g)
-        rows.extend(range(blk * 32, min(blk * 32 + 32, Nq)))
+    for j in range(4):
+        for blk in (4 * g + j, 8 * G - 1 - 4 * g - j):
+            rows.extend(range(blk * 32, min(blk * 32 + 32, Nq)))
     return rows
 
 
@@ -210,6 +210,14 @@ def test_mode_heuristic_and_override(lib, monkeypatch):
     assert fa.fa_fwd_plan(1, 4, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT       # 64 wide blocks: too few
     assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 32, 131072, 131072, 128, 1, 1).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(4, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD  # four full rounds
+    assert fa.fa_fwd_plan(5, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE       # more: dynamic dispatch
+    assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_SPLIT      # 1.25 rounds: fold would idle
+    assert fa.fa_fwd_plan(1, 32, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT      # two rounds of long chains
+    assert fa.fa_fwd_plan(2, 32, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(1, 8, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_SPLIT
+    assert fa.fa_fwd_plan(1, 16, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 0, 0).mode == fa.FA_MODE_WIDE       # not causal: nothing to even out
     monkeypatch.setenv("FA_FWD_MODE", "wide")
     assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).lds_bytes == 4 * 64 * 64 * 2
