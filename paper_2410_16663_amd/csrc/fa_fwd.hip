@@ -2,22 +2,28 @@
 //
 // Dataflow (FastAttention appendix A, the FlashAttention2 forward): for each block of
 // queries, walk the key/value blocks once; per block compute the logits on the matrix
-// cores, exponentiate against a running row maximum, multiply by V on the matrix cores,
-// and carry the running row maximum / row sum.  Mask handling follows section 4.1:
-// blocks that are entirely masked are skipped, blocks that are entirely visible take no
-// mask, and only blocks straddling the diagonal (or the ragged end of K) get a
-// per-element predicate computed from indices -- no mask tensor exists.
+// cores, exponentiate against a running reference, multiply by V on the matrix cores,
+// and carry the reference / row sum.  Mask handling follows section 4.1: blocks that are
+// entirely masked are skipped, blocks that are entirely visible take no mask, and only the
+// others get a per-element predicate computed from indices -- no mask tensor exists.
 //
-// gfx950 mapping (this file's own design):
-//  * one wavefront owns 32 query rows.  A workgroup is 8 wavefronts on 128 query rows: two
-//    groups of four, both groups on the same rows; group 0 takes the even 64-key tiles and
-//    group 1 the odd ones, and their partial results (accumulator, exponent reference, row
-//    sum) are merged through LDS at the end.  Each SIMD thus holds one wavefront of each
-//    group.  A wavefront cannot issue vector work while its own matrix instruction runs, so
-//    overlap of the matrix and vector units comes from the two groups being in opposite
-//    phases: while one group runs its matrix cluster (Q K^T of its tile and P V of its
-//    previous tile) the other runs its vector cluster (softmax of its tile); workgroup
-//    barriers between the clusters keep the two in step.
+// What is in this file:
+//  * fa_fwd_kernel -- the attention kernel, one source for every variant (template flags):
+//    WIDE (256 query rows per workgroup, all eight waves walk the same tiles) or split (128 rows,
+//    two groups of four waves on alternate tiles, merged through LDS); CAUSAL; SPLITKV (one run of
+//    the key tiles per workgroup, unnormalised result to a workspace); GENMASK (window / prefix /
+//    key-count masks from a descriptor).  Entry points fa_fwd, fa_fwd_splitkv, fa_fwd_masked.
+//  * fa_combine_kernel -- merges the split-KV runs.
+//  * fa_linear_kernel -- the output projection that follows the attention block by block
+//    (section 4.2), entry points fa_attn_linear_block / fa_attn_linear.
+//  * the host side: argument checks, choice of decomposition, launch shapes, and the
+//    host-callable copies of the scheduling logic (fa_fwd_plan, fa_mask_*).
+//
+// gfx950 mapping common to all variants (this file's own design):
+//  * one wavefront owns 32 query rows; a workgroup is 8 wavefronts, two per SIMD.  A wavefront
+//    cannot issue vector work while its own matrix instruction runs, so overlap of the matrix
+//    and vector units comes from the two wavefronts of a SIMD being in different phases; they
+//    run free between the one workgroup barrier per tile.
 //  * logits are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: keys on the
 //    M side (A operand, read from LDS with ds_read_b128), queries on the N side (B
 //    operand, held in registers for the whole kernel).  A lane then owns ONE query
@@ -28,7 +34,7 @@
 //  * V^T fragments come straight out of the row-major V tile with the transposing LDS
 //    read ds_read_b64_tr_b16.
 //  * K and V tiles (64 keys) go from global memory straight into LDS (global_load_lds),
-//    double-buffered per group, issued two clusters before they are needed.
+//    double-buffered (three-deep for split-KV), bank-swizzled on the global side.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
