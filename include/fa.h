@@ -162,7 +162,10 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
  * attention output in its own [B,H,Nq,D] layout; o is rounded to `dtype` in between, products
  * accumulate in fp32).  No allocation, no workspace, no synchronisation: a caller overlaps
  * communication by enqueueing it on another stream behind an event recorded after this call.
- * Calls for different blocks are independent.  Error behaviour as for fa_fwd.
+ * Calls for different blocks are independent.  Error behaviour as for fa_fwd.  The GEMM's
+ * workgroup tile is 256 tokens x 256 outputs when that still gives each of the 256 compute units
+ * a workgroup (B * ceil(row_count/256) * N/256 >= 256), else 128 x 256; the environment variable
+ * FA_LINEAR_TILE=128|256 overrides (tests, tuning).
  *
  * fa_attn_linear -- every block in order on one stream: blocks of rows_per_block rows, the first
  * one half that size (nothing can overlap with the first block); rows_per_block <= 0: one block.

@@ -820,13 +820,19 @@ struct LinParams {
     int ntile_total, per_xcd;
 };
 
-template <int DT, int D>
+template <int DT, int D, int BM>
 __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
-    constexpr int BM = 128, BNO = 256, BK = 64;
-    constexpr int A_TILE = BM * BK * 2;           // 16 KiB
+    static_assert(BM == 128 || BM == 256, "token rows per workgroup tile");
+    constexpr int BNO = 256, BK = 64;
+    constexpr int MB = BM / 64;                   // 32-row blocks per wave (wave tile BM/2 x 64)
+    constexpr int A_TILE = BM * BK * 2;           // 16 / 32 KiB
     constexpr int W_TILE = BK * BNO * 2;          // 32 KiB
     constexpr int STAGE = A_TILE + W_TILE;
-    constexpr int NST = 3;                        // tile buffers: loads run two k-tiles ahead (144 KiB)
+    // tile buffers: the small tile runs its loads two k-tiles ahead (3 x 48 KiB), the large one, whose
+    // iterations are twice as long, one ahead (2 x 64 KiB)
+    constexpr int NST = BM == 128 ? 3 : 2;
+    constexpr int NA = BM / 64;                   // o-tile load instructions per wave and k-tile
+    constexpr int PER_TILE = NA + 4;              // ... all load instructions per wave and k-tile
     __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
 
     const int tid = threadIdx.x;
@@ -848,13 +854,13 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
 
     const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, smem));
 
-    // ---- loads.  o tile: instruction i (1 KiB) fills rows 8i..8i+7; this wave issues i = wave and wave + 8.
+    // ---- loads.  o tile: instruction i (1 KiB) fills rows 8i..8i+7; this wave issues i = wave + 8n.
     // The lane that owns LDS slot (row r, chunk c') fetches global chunk c' ^ ((r >> 1) & 7).  Rows past the
     // end of the block are clamped to its last row (computed, never stored).
     const int a_r = lane >> 3, a_c = lane & 7;
-    unsigned a_voff[2];
+    unsigned a_voff[NA];
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
+    for (int n = 0; n < NA; ++n) {
         const int r = (wave + 8 * n) * 8 + a_r;
         const int s = p.s0 + min(r0 + r, p.rows - 1);
         a_voff[n] = (unsigned)(s * (D * 2) + ((a_c ^ ((r >> 1) & 7)) << 4));
@@ -876,7 +882,7 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
         const unsigned char *ag = ob + ((size_t)(b * p.H + hh) * p.q_rows * D + d0) * 2;
         const unsigned char *wg = wb + (size_t)k0 * p.N * 2;
 #pragma unroll
-        for (int n = 0; n < 2; ++n)
+        for (int n = 0; n < NA; ++n)
             dma16_to_lds<0>(uniform_ptr(ag), a_voff[n], lds_base + st * STAGE + (wave + 8 * n) * 1024);
 #pragma unroll
         for (int n = 0; n < 4; ++n)
@@ -885,7 +891,7 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
 
     // ---- operand fragments
     auto a_frag = [&](const unsigned char *as, int mb, int ks) __attribute__((always_inline)) -> s16x8 {
-        return *(const s16x8 *)(as + k_lds_off<64>(wm * 64 + mb * 32 + l32, 2 * ks + h));
+        return *(const s16x8 *)(as + k_lds_off<64>(wm * (BM / 2) + mb * 32 + l32, 2 * ks + h));
     };
     // k-slot (h, v) of 16-step ks is k = 16 ks + 8 h + v: two transposing reads of 4 k-rows x 16 outputs
     const int g2 = (lane >> 4) & 1, li = lane & 15, vi = li >> 2, vc = li & 3;
@@ -897,30 +903,32 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MB][2];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = (f32x16)(0.f);
 
-    // k-tile kt lives in buffer kt % 3.  Iteration kt issues the loads of tile kt + 2 (into the buffer tile
-    // kt - 1 used: every wave has passed the barrier that ended iteration kt - 1), works on tile kt, then waits
-    // until its own share of tile kt + 1 has landed (loads complete in order: all but the newest six) and
-    // meets the other waves.
-    load_tiles(0, 0);
-    if (KT > 1) load_tiles(1, 1);
-    if (KT > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 6);
+    // k-tile kt lives in buffer kt % NST and is loaded NST - 1 iterations ahead.  Iteration kt issues the loads
+    // of tile kt + NST - 1 (into the buffer tile kt - 1 used: every wave has passed the barrier that ended
+    // iteration kt - 1), works on tile kt, then waits until its own share of tile kt + 1 has landed (loads
+    // complete in order: all but the newest NST - 2 tiles' worth) and meets the other waves.
+    constexpr int PD = NST - 1;
+#pragma unroll
+    for (int t = 0; t < PD; ++t)
+        if (t < KT) load_tiles(t, t);
+    if (PD == 2 && KT > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | PER_TILE);
     else __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
     int st = 0;
     for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 2 < KT;
-        if (more) load_tiles(kt + 2, st >= 1 ? st - 1 : 2);
+        const bool more = kt + PD < KT;
+        if (more) load_tiles(kt + PD, st >= 1 ? st - 1 : NST - 1);
         const unsigned char *as = smem + st * STAGE;
         const unsigned char *ws = as + A_TILE;
-        s16x8 af[2][2], wf[2][2];          // [ks parity][block]
-        af[0][0] = a_frag(as, 0, 0);
-        af[0][1] = a_frag(as, 1, 0);
+        s16x8 af[2][MB], wf[2][2];          // [ks parity][block]
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) af[0][mb] = a_frag(as, mb, 0);
         wf[0][0] = w_frag(ws, 0, 0);
         wf[0][1] = w_frag(ws, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -928,30 +936,30 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
         for (int ks = 0; ks < 4; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
             if (ks + 1 < 4) {
-                af[nxt][0] = a_frag(as, 0, ks + 1);
-                af[nxt][1] = a_frag(as, 1, ks + 1);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) af[nxt][mb] = a_frag(as, mb, ks + 1);
                 wf[nxt][0] = w_frag(ws, ks + 1, 0);
                 wf[nxt][1] = w_frag(ws, ks + 1, 1);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32<DT>(af[cur][mb], wf[cur][nb], acc[mb][nb]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) __builtin_amdgcn_s_waitcnt(0x0F70 | 6);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (more && PD == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | PER_TILE);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __builtin_amdgcn_s_barrier();
-        st = st == 2 ? 0 : st + 1;
+        st = st == NST - 1 ? 0 : st + 1;
     }
 
     // ---- store: register r of block (mb, nb) is token row 8 (r/4) + 4 h + r%4, output column l32
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = r0 + wm * 64 + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            const int row = r0 + wm * (BM / 2) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
             if (row < p.rows) {
                 float *yp = p.y + ((size_t)b * p.q_rows + p.s0 + row) * p.N + n0 + wn * 64 + l32;
 #pragma unroll
@@ -1132,8 +1140,9 @@ hipError_t launch_attention(const FaParams &p, int mode, int D, int causal, int 
 }
 
 template <int DT, int D>
-hipError_t launch_linear(const LinParams &p, hipStream_t stream) {
-    hipLaunchKernelGGL((fa_linear_kernel<DT, D>), dim3(p.per_xcd * 8), dim3(512), 0, stream, p);
+hipError_t launch_linear(const LinParams &p, int BM, hipStream_t stream) {
+    if (BM == 256) hipLaunchKernelGGL((fa_linear_kernel<DT, D, 256>), dim3(p.per_xcd * 8), dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((fa_linear_kernel<DT, D, 128>), dim3(p.per_xcd * 8), dim3(512), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -1378,18 +1387,22 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
         lp.N = N;
         lp.s0 = row_first;
         lp.rows = row_count;
-        lp.mt_per_b = (row_count + 127) / 128;
         lp.n_tiles = N / 256;
+        // 256-row tiles (less LDS traffic per matrix instruction, twice the work per barrier) when they still
+        // give every compute unit a workgroup; FA_LINEAR_TILE=128|256 overrides (tests, tuning)
+        int BM = (long long)B * ((row_count + 255) / 256) * lp.n_tiles >= 256 ? 256 : 128;
+        if (const char *env = getenv("FA_LINEAR_TILE")) BM = !strcmp(env, "256") ? 256 : (!strcmp(env, "128") ? 128 : BM);
+        lp.mt_per_b = (row_count + BM - 1) / BM;
         const long long tiles = (long long)B * lp.mt_per_b * lp.n_tiles;
         if (tiles > 0x7ffffff0LL) return FA_ERR_SHAPE;
         lp.ntile_total = (int)tiles;
         lp.per_xcd = (int)((tiles + 7) / 8);
         hipError_t e;
         switch ((dtype << 1) | (D == 128)) {
-            case 0: e = launch_linear<0, 64>(lp, st); break;
-            case 1: e = launch_linear<0, 128>(lp, st); break;
-            case 2: e = launch_linear<1, 64>(lp, st); break;
-            default: e = launch_linear<1, 128>(lp, st); break;
+            case 0: e = launch_linear<0, 64>(lp, BM, st); break;
+            case 1: e = launch_linear<0, 128>(lp, BM, st); break;
+            case 2: e = launch_linear<1, 64>(lp, BM, st); break;
+            default: e = launch_linear<1, 128>(lp, BM, st); break;
         }
         if (e != hipSuccess) {
             g_last_hip_error = (int)e;

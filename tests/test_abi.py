@@ -244,8 +244,8 @@ def test_build_report_shows_register_only_kernels():
     from paper_2410_16663_amd import build
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
-    # combine: 2 dtypes x 2 head dims; output projection: 2 dtypes x 2 head dims
-    assert len(build.last_report) == 24 + 4 + 4 + 4
+    # combine: 2 dtypes x 2 head dims; output projection: 2 dtypes x 2 head dims x 2 tile heights
+    assert len(build.last_report) == 24 + 4 + 4 + 8
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

@@ -36,6 +36,13 @@ def check_y(y, y_ref, label):
     assert err.mean() <= Y_MEAN_ABS, f"{label}: y mean-abs {err.mean():.3e}"
 
 
+@pytest.fixture(params=["128", "256"], autouse=True)
+def tile(request, monkeypatch):
+    """Force each workgroup tile height of the projection kernel in turn (FA_LINEAR_TILE of include/fa.h)."""
+    monkeypatch.setenv("FA_LINEAR_TILE", request.param)
+    return request.param
+
+
 # B, H, Nq, Nk, D, N
 SHAPES = [(1, 2, 300, 300, 64, 256), (2, 3, 200, 333, 128, 512), (1, 4, 130, 130, 128, 256), (2, 2, 1, 500, 64, 256),
           (1, 1, 257, 129, 128, 768)]
@@ -98,8 +105,8 @@ def test_llama7b_layer_shape_on_sampled_tokens(oracle):
     print("case attn_linear C2 + 4096x4096 projection", flush=True)
     q, k, v = I.make_qkv(cfg)
     w = I.normal_bits((cfg.H * cfg.D, 4096), 2003, cfg.dtype, 1.0 / math.sqrt(cfg.H * cfg.D))
-    o, lse, y = run_attn_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows_per_block=512)
-    rows = np.array([0, 1, 127, 128, 255, 256, 300, 511, 512, 1000, 1023, 1024, 1500, 1535, 1536, 2047])
+    o, lse, y = run_attn_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows_per_block=1024)
+    rows = np.array([0, 1, 127, 128, 255, 256, 300, 511, 512, 1000, 1023, 1024, 1500, 1535, 1536, 2047])   # blocks start at 0, 512, 1536
     y_ref = oracle.attention_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows=rows)
     check_y(y[0, rows], y_ref, "C2 projection sample")
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
