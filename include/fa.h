@@ -73,9 +73,10 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * FA_MODE_SPLIT: a workgroup owns 128 query rows and its two wave groups take alternate
  * 64-key tiles; FA_MODE_WIDE: a workgroup owns 256 query rows and all its waves walk the same
  * tiles; FA_MODE_WIDE_FOLD (causal only): WIDE with each workgroup's eight 32-row blocks taken
- * four from the cheap end of the sequence and four, mirrored, from the expensive end.
+ * four from the cheap end of the sequence and four, mirrored, from the expensive end; once the
+ * cheap blocks are done their waves take every other tile of the expensive ones.
  * With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256; for causal problems with
- * Nq > 256: WIDE_FOLD when Nq <= 2048, W <= 1024 and the last round of 256 workgroups is at
+ * Nq > 768: WIDE_FOLD when Nq <= 4096, W <= 1024 and the last round of 256 workgroups is at
  * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); WIDE otherwise.
  * The environment variable FA_FWD_MODE=split|wide|fold overrides the choice (tests, tuning).
  */

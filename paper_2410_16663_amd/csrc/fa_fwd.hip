@@ -73,7 +73,6 @@ struct FaParams {
     int per_xcd;    // ceil(nwork / 8)
     float c;        // |scale| * log2(e), or 1 when scale == 0
     int qmode;      // 0: use q as is, 1: negate q (scale < 0), 2: zero q (scale == 0)
-    int fold;       // wide mode, causal: deal 32-row blocks to the waves in a folded order (see fold_block)
     // split-KV only: the keys of every query block are cut into nsplit runs of tiles, one
     // workgroup each (blockIdx.y); a workgroup leaves its unnormalised accumulator, exponent
     // reference and row sum here for the combine kernel
@@ -151,17 +150,16 @@ __host__ __device__ inline TileSeq tile_sequence(const MaskGeom &g, int R0, int 
     return {p_t, w_lo, p_t + (w_hi - w_lo + 1)};
 }
 
-// Folded row assignment (wide mode, causal, few workgroups).  A head's rows are cut into 8 G
-// blocks of 32 rows (G = workgroups per head); block i needs about i/2 + 1 key tiles.  Workgroup g
-// owns the four blocks 4g .. 4g+3 from the cheap end and their mirror images 8G-1-4g-j from the
-// expensive end, so every workgroup carries the same amount of triangular work.  Wave w < 4 takes
-// cheap block 4g + w, and wave w + 4 -- the wave it shares a SIMD with -- the mirror image of it.
-// All four SIMDs of a workgroup then hold the same kind of pair (one short walk, one long walk of
-// nearly equal lengths across the SIMDs): the waves meet at a barrier per tile, so an iteration costs
-// what its busiest SIMD costs, and with like pairs no SIMD is still running two waves after the
-// others have dropped to one.  (Dealing one block of every eighth of the sequence to each workgroup
-// balances the work just as well but mixes pairs of 4+32 ... 16+20 tiles in one workgroup: measured
-// 25% slower.)
+// Folded row assignment (causal, few rounds of workgroups; kernel variant PAIR).  A head's rows are cut
+// into 8 G blocks of 32 rows (G = workgroups per head); block i needs about i/2 + 1 key tiles.
+// Workgroup g owns the four blocks 4g .. 4g+3 from the cheap end and their mirror images 8G-1-4g-j
+// from the expensive end, so every workgroup carries the same amount of triangular work.  Wave w < 4
+// takes cheap block 4g + w, and wave w + 4 -- the wave it shares a SIMD with -- the mirror image of it.
+// All four SIMDs of a workgroup then hold the same kind of pair: the waves meet at a barrier per tile,
+// so an iteration costs what its busiest SIMD costs, and with like pairs no SIMD is still running two
+// waves after the others have dropped to one.  (Dealing one block of every eighth of the sequence to
+// each workgroup balances the work just as well but mixes pairs of 4+32 ... 16+20 tiles in one
+// workgroup: measured 8% slower, before the finished waves were put to work.)
 __host__ __device__ inline int fold_block(int G, int g, int w) {
     return w < 4 ? 4 * g + w : 8 * G - 1 - 4 * g - (w - 4);
 }
@@ -289,9 +287,17 @@ __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, u
 //   blocks alone cannot fill the chip.
 // GENMASK = true (wide only, CAUSAL = false): the mask comes from the descriptor in p (window,
 //   prefix, per-batch key count) instead of the causal flag; see MaskGeom.
-template <int DT, int D, bool CAUSAL, bool WIDE, bool SPLITKV = false, bool GENMASK = false>
+// PAIR = true (wide, causal only): the folded decomposition for short causal problems, see fold_block.  The
+//   two waves of a SIMD hold a cheap block and its expensive mirror image.  Once the cheap blocks are done
+//   (phase A, one tile per iteration), their waves store their rows, take over the Q rows of their SIMD
+//   partner and the workgroup loads TWO tiles per iteration (phase B): the partner takes the odd ones, the
+//   helper the even ones, and the two partial results are merged through LDS at the end.  Without this the
+//   long blocks' waves would walk their last tiles alone on their SIMDs, where a lone wave cannot overlap its
+//   own matrix and vector work.
+template <int DT, int D, bool CAUSAL, bool WIDE, bool SPLITKV = false, bool GENMASK = false, bool PAIR = false>
 __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     static_assert(WIDE || !SPLITKV, "split-KV is built on the wide decomposition");
+    static_assert(!PAIR || (WIDE && CAUSAL && !SPLITKV && !GENMASK), "the paired fold is a causal wide decomposition");
     static_assert(!GENMASK || (WIDE && !SPLITKV && !CAUSAL), "descriptor masks are built on the plain wide decomposition");
     constexpr int NWL = WIDE ? 8 : 4;             // waves that load one tile together
     constexpr int BM = WIDE ? 256 : 128;          // query rows per workgroup
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int NSTAGE = SPLITKV ? FA_SPLITKV_STAGES : (WIDE ? FA_WIDE_STAGES : 2);
     constexpr bool LOADS_FIRST = SPLITKV || FA_LOADS_FIRST;
     constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
-    constexpr int NSETS = WIDE ? 1 : 2;           // split mode: one set per group
+    constexpr int NSETS = (WIDE && !PAIR) ? 1 : 2;   // split mode: one set per group; paired fold: one per tile of an iteration
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[NSETS * GROUPB];
 
@@ -338,7 +344,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     const int off = p.off;                        // key on the diagonal of query row 0 (Nk - Nq for a whole-q launch)
     int q_wave = qt * BM + wq * 32;               // first query row of this wave
     int last_row_wg = min(qt * BM + BM - 1, Nq - 1);   // last query row of the workgroup
-    if (WIDE && CAUSAL && p.fold) {
+    if constexpr (PAIR) {
         q_wave = fold_block(p.nqt, qt, wq) * 32;
         last_row_wg = -1;
 #pragma unroll
@@ -347,7 +353,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             if (first < Nq) last_row_wg = max(last_row_wg, min(first + 31, Nq - 1));
         }
     }
-    const int qrow = q_wave + l32;                // this lane's query row
+    int qrow = q_wave + l32;                      // this lane's query row
 
     int kmax_wg = Nk - 1, kmax_wave = Nk - 1;     // last key index any row may see
     if (CAUSAL) {
@@ -381,8 +387,11 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         nj_loop = nt;
     }
     // position j of this group's walk -> tile index
+    // paired fold: the tile this wave works on in the current iteration, and how many tiles its block needs
+    int pair_tile = 0, pair_need = 0;
     auto tile_of = [&](int j) __attribute__((always_inline)) -> int {
         if constexpr (GENMASK) return j < seq.np ? j : seq.base + (j - seq.np);
+        if constexpr (PAIR) return pair_tile;
         return t_lo + TSTEP * j + grp;
     };
     // ... -> does this wave work on it, and does it need the per-element predicate
@@ -392,6 +401,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             cls_cur = tile_class(wt, tile_of(j));
             return cls_cur != TILE_SKIP;
         }
+        if constexpr (PAIR) return pair_tile < pair_need;
         return j < n_act;
     };
 
@@ -401,7 +411,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds d = 16*kb + 8*h + 0..7 of its row
     s16x8 qf[KB];
-    {
+    auto load_q = [&]() __attribute__((always_inline)) {
         const uint16_t *qp = p.q + ((size_t)bh * p.q_rows + (qrow < Nq ? qrow : 0)) * D + 8 * h;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
@@ -410,7 +420,8 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             if (p.qmode == 1) x ^= (s16x8)((short)0x8000);
             qf[kb] = x;
         }
-    }
+    };
+    load_q();
 
     // ---- K/V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per
     // lane, no staging registers).  One such instruction fills 1 KiB of LDS contiguously in
@@ -432,6 +443,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     const int k_voff = ld_row0 * ROWB + ck * 16;  // per-lane byte offset of the K chunk within the tile (first instruction)
     const int v_voff = ld_row0 * ROWB + cv * 16;  // same for V
     unsigned char *gsm = smem + grp * GROUPB;     // this group's buffers
+    const unsigned char *rsm = gsm;               // ... as read by the matrix clusters (paired fold: switches sets)
     const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)LDS_PTR(unsigned char, gsm));
     // whole tiles take their per-lane offsets as they are (tile start and instruction step go
     // into the scalar base); the ragged last tile clamps its rows to the last key -- those rows
@@ -502,7 +514,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- S^T = K(j) Q^T for group tile j (K buffer ST = j % NSTAGE)
     auto qk_cluster = [&](auto st_c) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;
-        const unsigned char *ks = gsm + ST * TILEB;
+        const unsigned char *ks = rsm + ST * TILEB;
         s16x8 fr[2 * KB];
 #pragma unroll
         for (int i = 0; i < LA; ++i) fr[i] = k_frag(ks, i & 1, i >> 1);
@@ -519,7 +531,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // ---- O^T += V(j)^T P(j)^T (V buffer ST = j % NSTAGE)
     auto pv_cluster = [&](auto st_c) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;
-        const unsigned char *vs = gsm + (NSTAGE + ST) * TILEB;
+        const unsigned char *vs = rsm + (NSTAGE + ST) * TILEB;
         s16x8 fr[4 * DB];
 #pragma unroll
         for (int i = 0; i < LA; ++i) fr[i] = v_frag(vs, i / DB, i % DB);
@@ -637,6 +649,26 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         }
     };
 
+    // ---- result of this wave's rows: combine the two half-wave sums, normalise, store
+    auto store_rows = [&]() __attribute__((always_inline)) {
+        const float l_tot = xhalf_sum(l_run);
+        if (qrow < Nq) {
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            uint16_t *op = p.o + ((size_t)bh * p.q_rows + qrow) * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const s16x2 a = pack2<DT>(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
+                    const s16x2 b = pack2<DT>(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
+                    const s16x4 st = {a[0], a[1], b[0], b[1]};
+                    *(s16x4 *)(op + db * 32 + 8 * g) = st;
+                }
+            if (h == 0)
+                p.lse[(size_t)bh * p.q_rows + qrow] = l_tot > 0.f ? (m_ref + __log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+        }
+    };
+
     // ---- pipeline.  Tiles are loaded PD = NSTAGE-1 iterations ahead.  Iteration j: each group
     // issues the loads of its tile j+PD (into the buffer tile j-1 used), works on its tile j
     // (logits, softmax, P V), waits until its share of tile j+1 has landed and meets the other
@@ -644,12 +676,173 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int PD = NSTAGE - 1;
     constexpr int PER_TILE = 2 * NI;              // load instructions a wave issues per tile (K and V)
     static_assert(NINSTR % NWL == 0, "every wave must issue the same number of loads per tile");
+    using std::integral_constant;
+    if constexpr (PAIR) {
+        // ---- paired fold.  helper = the wave that starts on a cheap block (waves 0..3); its SIMD partner
+        // (wave + 4) owns the mirror image.  Phase A: iterations 0 .. nA-1, tile j for everybody (set 0).
+        // Phase B: iteration nA + i loads tiles nA + 2i (set 0, the helper's) and nA + 2i + 1 (set 1, the
+        // owner's).  Tiles are loaded one iteration ahead into stage (iteration & 1) of their set.
+        static_assert(NSTAGE == 2, "the paired fold alternates two stages");
+        const bool helper = wave < 4;
+        auto tiles_of_block = [&](int blk) __attribute__((always_inline)) -> int {
+            const int first = blk * 32;
+            if (first >= Nq) return 0;
+            const int kmax = min(Nk - 1, min(first + 31, Nq - 1) + off);
+            return kmax >= 0 ? kmax / BN + 1 : 0;
+        };
+        const int blk_long = fold_block(p.nqt, qt, (wave & 3) + 4);
+        int nA = 0;                                  // tiles the workgroup's cheap blocks need (they grow with the block index)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) nA = max(nA, tiles_of_block(fold_block(p.nqt, qt, w)));
+        const int L = nt;                            // tiles the workgroup walks in all
+        const int nB = (max(L - nA, 0) + 1) / 2;
+        const int NJ = nA + nB;
+        pair_need = tiles_of_block(fold_block(p.nqt, qt, wave));
+        // loads of iteration jn (both tensors, every wave its share); nothing to load past the last tile
+        auto issue_loads = [&](int jn, int stl) __attribute__((always_inline)) {
+            if (jn >= NJ) return;
+            if (jn < nA) {
+                load_tile(kgb, jn, stl * TILEB, std::true_type{}, std::false_type{});
+                load_tile(vgb, jn, (NSTAGE + stl) * TILEB, std::false_type{}, std::false_type{});
+            } else {
+                const int t0 = nA + 2 * (jn - nA);
+                load_tile(kgb, t0, stl * TILEB, std::true_type{}, std::false_type{});
+                load_tile(vgb, t0, (NSTAGE + stl) * TILEB, std::false_type{}, std::false_type{});
+                if (t0 + 1 < L) {
+                    load_tile(kgb, t0 + 1, GROUPB + stl * TILEB, std::true_type{}, std::false_type{});
+                    load_tile(vgb, t0 + 1, GROUPB + (NSTAGE + stl) * TILEB, std::false_type{}, std::false_type{});
+                }
+            }
+        };
+        auto pair_iteration = [&](auto st_c, int jj) __attribute__((always_inline)) {
+            constexpr int ST = decltype(st_c)::value;
+            if (jj == nA) {
+                // the cheap blocks are done: their waves store them and join their partners' blocks;
+                // the partners read their tiles from set 1 from now on
+                if (helper) {
+                    store_rows();
+                    q_wave = blk_long * 32;
+                    qrow = q_wave + l32;
+                    load_q();
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) oacc[db] = (f32x16)(0.f);
+                    m_ref = -1e30f;
+                    l_run = 0.f;
+                    pair_need = tiles_of_block(blk_long);
+                } else {
+                    rsm = smem + GROUPB;
+                }
+            }
+            pair_tile = jj < nA ? jj : nA + 2 * (jj - nA) + (helper ? 0 : 1);
+            if (pair_tile < pair_need) {
+                qk_cluster(st_c);
+                issue_loads(jj + 1, ST ^ 1);
+                softmax_cluster(jj, std::true_type{});
+                pv_cluster(st_c);
+            } else {
+                issue_loads(jj + 1, ST ^ 1);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+        };
+        // phase-B iteration without checks: this wave's tile is needed, unmasked and wholly inside K/V, and
+        // both tiles of the next iteration exist and lie wholly inside K/V
+        auto pair_interior = [&](auto st_c, int jj) __attribute__((always_inline)) {
+            constexpr int ST = decltype(st_c)::value;
+            pair_tile = nA + 2 * (jj - nA) + (helper ? 0 : 1);
+            qk_cluster(st_c);
+            const int t0 = nA + 2 * (jj + 1 - nA);
+            load_tile(kgb, t0, (ST ^ 1) * TILEB, std::true_type{}, std::true_type{});
+            load_tile(vgb, t0, (NSTAGE + (ST ^ 1)) * TILEB, std::false_type{}, std::true_type{});
+            load_tile(kgb, t0 + 1, GROUPB + (ST ^ 1) * TILEB, std::true_type{}, std::true_type{});
+            load_tile(vgb, t0 + 1, GROUPB + (NSTAGE + (ST ^ 1)) * TILEB, std::false_type{}, std::true_type{});
+            softmax_cluster(jj, std::false_type{});
+            pv_cluster(st_c);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+        };
+        // iterations nA+1 .. jI-1 are of that kind for this wave (iteration nA holds the switch); slot = which
+        // of an iteration's two tiles is this wave's in phase B
+        int jI = 0;
+        {
+            const int slot = helper ? 0 : 1;
+            const int free_key = min(Nk - 1, blk_long * 32 + off);            // last key the block's first row sees
+            const int t_unmasked = free_key >= BN - 1 ? (free_key - (BN - 1)) / BN : -1;   // last tile without a mask
+            const int t_loadable = min(L, Nk / BN) - 1;                            // last tile that is walked and whole
+            // i-th phase-B iteration: own tile nA + 2i + slot <= t_unmasked, next iteration's second tile
+            // nA + 2i + 3 <= t_loadable
+            const int a = t_unmasked - nA - slot, b = t_loadable - nA - 3;
+            const int i_last = min(a >= 0 ? a / 2 : -1, b >= 0 ? b / 2 : -1);
+            jI = blk_long * 32 < Nq ? nA + i_last + 1 : 0;
+        }
+        issue_loads(0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        // general iterations up to the first even one after the switch, check-free ones in whole pairs, general rest
+        const int i_first = min((nA + 2) & ~1, NJ);
+        const int i_end = jI > i_first ? i_first + ((jI - i_first) & ~1) : i_first;
+        int jj = 0;
+        if constexpr (D == 128) {   // (D = 64: the extra copies of the loop body would cost the fourth wave per SIMD)
+            for (; jj < i_first; jj += 2) {
+                pair_iteration(integral_constant<int, 0>{}, jj);
+                if (jj + 1 < i_first) pair_iteration(integral_constant<int, 1>{}, jj + 1);
+            }
+            for (; jj < i_end; jj += 2) {
+                pair_interior(integral_constant<int, 0>{}, jj);
+                pair_interior(integral_constant<int, 1>{}, jj + 1);
+            }
+        }
+        for (; jj < NJ; jj += 2) {
+            pair_iteration(integral_constant<int, 0>{}, jj);
+            if (jj + 1 < NJ) pair_iteration(integral_constant<int, 1>{}, jj + 1);
+        }
+        if (NJ <= nA && helper) {
+            // no phase B at all (the expensive blocks need no more tiles than the cheap ones): the switch never ran
+            store_rows();
+            q_wave = blk_long * 32;
+            qrow = q_wave + l32;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) oacc[db] = (f32x16)(0.f);
+            m_ref = -1e30f;
+            l_run = 0.f;
+        }
+        // ---- merge the helper's share of the expensive block into its owner's (all tile buffers are idle now).
+        // Lane-major layout: value k of pair w's lane sits at w*XW + k*256 + lane*4.
+        constexpr int NV = DB * 16 + 2;               // accumulator + m_ref + l_run
+        constexpr int XW = NV * 256;                  // bytes per wave
+        static_assert(4 * XW <= NSETS * GROUPB, "exchange area must fit in the tile buffers");
+        float *xch = (float *)(smem + (wave & 3) * XW) + lane;
+        if (helper) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(db * 16 + r) * 64] = oacc[db][r];
+            xch[(DB * 16) * 64] = m_ref;
+            xch[(DB * 16 + 1) * 64] = l_run;
+        }
+        __syncthreads();
+        if (helper) return;
+        {
+            const float m1 = xch[(DB * 16) * 64];
+            const float l1 = xch[(DB * 16 + 1) * 64];
+            const float m = fmaxf(m_ref, m1);
+            const float a0 = __builtin_amdgcn_exp2f(m_ref - m);
+            const float a1 = __builtin_amdgcn_exp2f(m1 - m);
+            l_run = l_run * a0 + l1 * a1;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] = oacc[db][r] * a0 + xch[(db * 16 + r) * 64] * a1;
+            m_ref = m;
+        }
+        store_rows();
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < PD; ++j)
         if (TSTEP * j + grp < nt) { load_k(j, j, std::false_type{}); load_v(j, j, std::false_type{}); }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __builtin_amdgcn_s_barrier();
-    using std::integral_constant;
     // general iteration: every condition checked
     auto iteration = [&](auto st_c, int j) __attribute__((always_inline)) {
         constexpr int ST = decltype(st_c)::value;             // j % NSTAGE
@@ -763,9 +956,9 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         }
     }
 
-    // ---- epilogue: combine the two half-wave sums, normalise, store
-    const float l_tot = xhalf_sum(l_run);
+    // ---- epilogue
     if constexpr (SPLITKV) {
+        const float l_tot = xhalf_sum(l_run);
         if (qrow < Nq) {
             const size_t row = (size_t)blockIdx.y * ((size_t)p.nwork / p.nqt) * Nq + (size_t)bh * Nq + qrow;
             float *po = p.part_o + row * D + 4 * h;
@@ -783,21 +976,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
         }
         return;
     }
-    if (qrow < Nq) {
-        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        uint16_t *op = p.o + ((size_t)bh * p.q_rows + qrow) * D + 4 * h;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const s16x2 a = pack2<DT>(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
-                const s16x2 b = pack2<DT>(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
-                const s16x4 st = {a[0], a[1], b[0], b[1]};
-                *(s16x4 *)(op + db * 32 + 8 * g) = st;
-            }
-        if (h == 0)
-            p.lse[(size_t)bh * p.q_rows + qrow] = l_tot > 0.f ? (m_ref + __log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
-    }
+    store_rows();
 }
 
 // ---- output projection (section 4.2: the Linear that follows the attention, computed block of rows by
@@ -1043,14 +1222,16 @@ int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
 }
 
 // Work decomposition for a problem, W = B * H * ceil(Nq / 256) being the number of 256-row workgroups
-// (the chip has 256 compute units and a D = 128 workgroup fills one).  Measured on causal problems:
+// (the chip has 256 compute units and a D = 128 workgroup fills one).  From a sweep of forced modes
+// over 19 causal shapes:
 //  * fewer workgroups than compute units: FA_MODE_SPLIT doubles their number and halves their chains;
-//  * causal, short sequences (Nq <= 2048), up to four rounds of workgroups that fill their last round
-//    to 85%: FA_MODE_WIDE_FOLD -- every workgroup carries the same triangular work, so whole rounds
-//    take equal time (7-17% faster than the others there; with a poorly filled last round it loses to
-//    the split mode, whose workgroups are half the size);
-//  * causal, longer sequences with few rounds (W < 640 up to Nq = 4096, W < 384 beyond): FA_MODE_SPLIT,
-//    whose shorter chains matter more than its extra K/V traffic (up to 29% faster than wide there);
+//  * causal, 1024 <= Nq <= 4096, up to four rounds of workgroups that fill their last round to 85%:
+//    FA_MODE_WIDE_FOLD -- every workgroup carries the same triangular work, so whole rounds take
+//    equal time, and the waves of finished cheap blocks help with the expensive ones (5-25% faster
+//    than the others there; with a poorly filled last round it loses to the split mode, whose
+//    workgroups are half the size);
+//  * causal, few rounds of long chains otherwise (W < 640 up to Nq = 4096, W < 384 beyond):
+//    FA_MODE_SPLIT, whose shorter chains matter more than its extra K/V traffic;
 //  * otherwise FA_MODE_WIDE: with many rounds the heavy-first dynamic dispatch evens out the triangle.
 // The environment variable FA_FWD_MODE ("split" / "wide" / "fold") overrides.
 int choose_mode(int B, int H, int Nq, int causal) {
@@ -1061,10 +1242,10 @@ int choose_mode(int B, int H, int Nq, int causal) {
     const long long nqt = ((long long)Nq + 255) / 256;
     const long long W = (long long)B * H * nqt;
     if (W < 256) return FA_MODE_SPLIT;
-    if (causal && nqt >= 2) {
+    if (causal && nqt >= 4) {
         const long long rounds = (W + 255) / 256;
         const bool fills_last_round = rounds * 256 * 100 <= W * 115;
-        if (Nq <= 2048 && W <= 1024 && fills_last_round) return FA_MODE_WIDE_FOLD;
+        if (Nq <= 4096 && W <= 1024 && fills_last_round) return FA_MODE_WIDE_FOLD;
         if (Nq <= 4096 ? W < 640 : W < 384) return FA_MODE_SPLIT;
     }
     return FA_MODE_WIDE;
@@ -1113,9 +1294,23 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
     return (int)n;
 }
 
-// the 16 plain instantiations: (split | wide) x dtype x head dimension x causal
+template <int DT, int D>
+hipError_t launch_pair(const FaParams &p, int nwork_padded, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, true, true, false, false, true>), dim3(nwork_padded), dim3(512), 0, stream, p);
+    return hipGetLastError();
+}
+
+// the plain instantiations: (split | wide) x dtype x head dimension x causal, and the paired fold (causal only)
 hipError_t launch_attention(const FaParams &p, int mode, int D, int causal, int dtype, int grid, hipStream_t st) {
     hipError_t e;
+    if (mode == FA_MODE_WIDE_FOLD && causal) {
+        switch ((dtype << 1) | (D == 128)) {
+            case 0: return launch_pair<0, 64>(p, grid, st);
+            case 1: return launch_pair<0, 128>(p, grid, st);
+            case 2: return launch_pair<1, 64>(p, grid, st);
+            default: return launch_pair<1, 128>(p, grid, st);
+        }
+    }
     const int key = ((mode != FA_MODE_SPLIT) << 3) | (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
         case 0: e = launch<0, 64, false, false>(p, grid, st); break;
@@ -1168,7 +1363,6 @@ FaParams base_params(const void *q, const void *k, const void *v, void *o, float
     const float LOG2E = 1.4426950408889634f;
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
-    p.fold = 0;
     p.nsplit = 1;
     p.part_o = nullptr;
     p.part_ml = nullptr;
@@ -1215,7 +1409,7 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     plan->work_items = nwork;
     plan->tiles_visited = visited * B * H;
     plan->tiles_total = nwork * tiles_k;
-    plan->lds_bytes = (mode == FA_MODE_SPLIT ? 2 : 1) * 4 * BN * D * 2;   // sets of 2+2 tiles
+    plan->lds_bytes = (mode == FA_MODE_WIDE ? 1 : 2) * 4 * BN * D * 2;    // sets of 2+2 tiles
     return FA_OK;
 }
 
@@ -1234,7 +1428,6 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     const long long nwork = (long long)B * H * nqt;
 
     FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, nqt, nwork, scale);
-    p.fold = mode == FA_MODE_WIDE_FOLD;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
@@ -1369,7 +1562,6 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
                                  lse + row_first, H, row_count, Nk, nqt, nwork, scale);
         p.q_rows = Nq;
         p.off = Nk - Nq + row_first;
-        p.fold = mode == FA_MODE_WIDE_FOLD;
         const hipError_t e = launch_attention(p, mode, D, causal, dtype, p.per_xcd * 8, st);
         if (e != hipSuccess) {
             g_last_hip_error = (int)e;

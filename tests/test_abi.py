@@ -213,8 +213,9 @@ def test_mode_heuristic_and_override(lib, monkeypatch):
     assert fa.fa_fwd_plan(4, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD  # four full rounds
     assert fa.fa_fwd_plan(5, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE       # more: dynamic dispatch
     assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_SPLIT      # 1.25 rounds: fold would idle
-    assert fa.fa_fwd_plan(1, 32, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT      # two rounds of long chains
-    assert fa.fa_fwd_plan(2, 32, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(1, 32, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD
+    assert fa.fa_fwd_plan(1, 40, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_WIDE       # 2.5 rounds: neither
+    assert fa.fa_fwd_plan(8, 32, 512, 512, 128, 1, 0).mode == fa.FA_MODE_WIDE         # two blocks per head: nothing to fold
     assert fa.fa_fwd_plan(1, 8, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_SPLIT
     assert fa.fa_fwd_plan(1, 16, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 0, 0).mode == fa.FA_MODE_WIDE       # not causal: nothing to even out
@@ -244,8 +245,8 @@ def test_build_report_shows_register_only_kernels():
     from paper_2410_16663_amd import build
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
-    # combine: 2 dtypes x 2 head dims; output projection: 2 dtypes x 2 head dims x 2 tile heights
-    assert len(build.last_report) == 24 + 4 + 4 + 8
+    # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile heights
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

@@ -47,6 +47,25 @@ def test_small_shapes_elementwise(oracle, mode, shape, causal, dtype):
     check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} causal={causal} dt={dtype}")
 
 
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("shape", [(1, 2, 2048, 2048, 128), (1, 1, 1500, 1500, 64), (1, 2, 1000, 1300, 128),
+                                   (1, 1, 1300, 1000, 128), (2, 1, 1025, 1025, 64), (1, 1, 4096, 4096, 128),
+                                   (1, 2, 777, 3000, 64)])
+def test_folded_mode_on_longer_causal_shapes(oracle, monkeypatch, shape, dtype):
+    """The paired fold has two phases, a mid-kernel change of blocks and a merge: shapes with several workgroups
+    per head, ragged ends, more keys than queries (phase A empty for the first workgroups) and fewer (rows
+    without keys, expensive blocks that need no second phase)."""
+    monkeypatch.setenv("FA_FWD_MODE", "fold")
+    B, H, Nq, Nk, D = shape
+    print(f"case fold shape={shape} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, dtype, 7)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, dtype)
+    o, lse = run_fa_fwd(q, k, v, scale, True, dtype)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"fold {shape} dt={dtype}")
+
+
 @pytest.mark.parametrize("scale", [-0.2, 0.0, 1.0, 1e-3])
 def test_unusual_scales(oracle, mode, scale):
     print(f"case mode={mode} scale={scale}", flush=True)
