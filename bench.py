@@ -240,8 +240,10 @@ def cpu_decode_entry(I, np):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
+    # defaults: about a second of launches on the headline workload; a run of a few tens of milliseconds ends
+    # before the GPU has reached its sustained clocks and reads 10% low
+    ap.add_argument("--steps", type=int, default=None, help="timed launches (default: 20000 for C1/C2, fewer for the long ones)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed launches before (default: a quarter of --steps)")
     ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
     ap.add_argument("--sliding-only", action="store_true",
                     help="time only the sliding-window workload through fa_fwd_masked (for profiling runs)")
@@ -257,6 +259,14 @@ def main():
                     help="also launch a plain device copy of this many MiB (a known-size reference "
                          "for the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = {"C1": 20000, "C2": 20000, "C3": 100, "C4": 400, "C5": 5}.get(args.workload, 50)
+        if args.decode_only:
+            args.steps = 2000
+        if args.sliding_only or args.projection_only:
+            args.steps = 200
+    if args.warmup is None:
+        args.warmup = max(1, args.steps // 4)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
         sys.exit(2)
