@@ -65,19 +65,22 @@ def test_whole_problem_in_blocks(oracle, shape, rows_per_block, causal, dtype):
     check_y(y, y_ref, f"{shape} rpb={rows_per_block}")
 
 
-def test_blocks_are_independent_and_touch_only_their_rows(oracle):
-    """Arbitrary blocks, out of order, leaving a gap: the gap's rows of o, lse, y stay as they were."""
-    print("case attn_linear arbitrary blocks", flush=True)
+@pytest.mark.parametrize("mode", ["split", "wide", "fold"])
+def test_blocks_are_independent_and_touch_only_their_rows(oracle, monkeypatch, mode):
+    """Arbitrary blocks, out of order, leaving a gap: the gap's rows of o, lse, y stay as they were.  Every
+    decomposition of the attention launch is run on a block whose first row is not row 0."""
+    monkeypatch.setenv("FA_FWD_MODE", mode)
+    print(f"case attn_linear arbitrary blocks mode={mode}", flush=True)
     rng = np.random.default_rng(601)
-    B, H, Nq, Nk, D, N = 2, 2, 400, 450, 128, 256
+    B, H, Nq, Nk, D, N = 2, 2, 1400, 1450, 128, 256
     q, k, v, w = make(rng, B, H, Nq, Nk, D, N, I.F16)
     scale = 0.09
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, I.F16)
     y_ref = oracle.attention_linear(q, k, v, w, scale, True, I.F16)
-    o, lse, y = run_attn_linear(q, k, v, w, scale, True, I.F16, blocks=[(300, 100), (0, 70), (70, 131)])
+    o, lse, y = run_attn_linear(q, k, v, w, scale, True, I.F16, blocks=[(800, 600), (0, 70), (70, 531)])
     done = np.zeros(Nq, dtype=bool)
-    done[0:201] = True
-    done[300:400] = True
+    done[0:601] = True
+    done[800:1400] = True
     check_against_oracle(o[:, :, done], lse[:, :, done], o_ref[:, :, done], lse_ref[:, :, done], I.F16, "blocks")
     check_y(y[:, done], y_ref[:, done], "blocks")
     assert np.isnan(y[:, ~done]).all() and np.isnan(lse[:, :, ~done]).all() and (o[:, :, ~done] == 0x7E00).all()
