@@ -306,19 +306,11 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     constexpr int DB = D / 32;                    // 32-row blocks of O^T
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;
-#ifndef FA_SPLITKV_STAGES
-#define FA_SPLITKV_STAGES 3
-#endif
-    // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead.  Two for the compute-bound shapes (3 measured
-    // slower); the split-KV shapes are bound by HBM latency x bandwidth and take a third
-#ifndef FA_WIDE_STAGES
-#define FA_WIDE_STAGES 2
-#endif
-#ifndef FA_LOADS_FIRST
-#define FA_LOADS_FIRST 0
-#endif
-    constexpr int NSTAGE = SPLITKV ? FA_SPLITKV_STAGES : (WIDE ? FA_WIDE_STAGES : 2);
-    constexpr bool LOADS_FIRST = SPLITKV || FA_LOADS_FIRST;
+    // tile buffers per tensor: tiles are loaded NSTAGE-1 ahead.  Two for the compute-bound shapes (three measured
+    // 3-10% slower there); the split-KV shapes are bound by HBM latency x bandwidth and take a third, and
+    // issue their loads first thing in an iteration instead of between the two matrix clusters
+    constexpr int NSTAGE = SPLITKV ? 3 : 2;
+    constexpr bool LOADS_FIRST = SPLITKV;
     constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
     constexpr int NSETS = (WIDE && !PAIR) ? 1 : 2;   // split mode: one set per group; paired fold: one per tile of an iteration
 
@@ -506,10 +498,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     f32x16 sreg[2];            // logits of the current tile (two 32-key blocks)
     s16x8 pf[4];               // its exponentials, packed, as B operands of the four 16-key steps
 
-#ifndef FA_LA
-#define FA_LA 2
-#endif
-    constexpr int LA = FA_LA;  // operand fragments are read this many matrix instructions ahead
+    constexpr int LA = 2;      // operand fragments are read this many matrix instructions ahead (1: 10% slower; 3, 4: no gain)
 
     // ---- S^T = K(j) Q^T for group tile j (K buffer ST = j % NSTAGE)
     auto qk_cluster = [&](auto st_c) __attribute__((always_inline)) {
