@@ -61,17 +61,24 @@ def time_config(cfg, tensors, steps, warmup, torch, fa):
     for _ in range(warmup):
         launch()
     torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
+    # HIP events on the stream the kernel is launched on: one pair around all the steps, and one event per chunk
+    # of steps (at most 20 chunks) for the spread
+    nchunk = min(20, steps)
+    bounds = [steps * i // nchunk for i in range(nchunk + 1)]
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(nchunk + 1)]
     t0 = time.perf_counter()
-    ev0.record(stream)          # HIP events on the stream the kernel is launched on
-    for _ in range(steps):
-        launch()
-    ev1.record(stream)
+    evs[0].record(stream)
+    for c in range(nchunk):
+        for _ in range(bounds[c + 1] - bounds[c]):
+            launch()
+        evs[c + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / steps
-    event_ms = ev0.elapsed_time(ev1) / steps
+    event_ms = evs[0].elapsed_time(evs[-1]) / steps
+    chunk_ms = sorted(evs[c].elapsed_time(evs[c + 1]) / (bounds[c + 1] - bounds[c]) for c in range(nchunk))
+    time_config.last_spread = {"chunks": nchunk, "min_ms": round(chunk_ms[0], 5),
+                               "median_ms": round(chunk_ms[len(chunk_ms) // 2], 5), "max_ms": round(chunk_ms[-1], 5)}
     return wall_ms, event_ms, (to, tl)
 
 
@@ -102,6 +109,27 @@ def time_decode(cfg, tensors, steps, warmup, torch, fa):
     ev1.record(stream)
     torch.cuda.synchronize()
     return ev0.elapsed_time(ev1) / steps, plan
+
+
+def mfma_ceiling(torch, fa, dtype):
+    """TFLOP/s of a kernel that issues nothing but matrix instructions (fa_mfma_probe), sustained for about 0.3 s:
+    what the chip delivers under its power limit, to quote beside the nominal peak."""
+    scratch = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    iters = 200000
+    for _ in range(2):
+        flops = fa.fa_mfma_probe(dtype, iters, scratch, sp)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    reps = 4
+    ev0.record(stream)
+    for _ in range(reps):
+        fa.fa_mfma_probe(dtype, iters, scratch, sp)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    return reps * flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
 
 
 def read_traffic(workload):
@@ -303,7 +331,9 @@ def main():
         tensors, host = device_inputs_on_gpu(cfg, torch), None
     else:
         tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
-    wall_ms, event_ms, _ = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
+    wall_ms, event_ms, outputs = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
+    spread = time_config.last_spread
+    ceiling = mfma_ceiling(torch, fa, cfg.dtype)
     flops = cfg.flops()
     plan = fa.fa_fwd_plan(cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, int(cfg.causal), cfg.dtype)
     value = flops / (wall_ms * 1e-3) / 1e12
@@ -315,7 +345,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if cfg.dtype == 0 else "bf16", "data": "synthetic",
         "pct_of_mfma_peak": round(100.0 * value / MFMA_PEAK_TFLOPS, 2),
+        "mfma_only_ceiling_tflops": round(ceiling, 1), "pct_of_mfma_only_ceiling": round(100.0 * value / ceiling, 2),
+        "launch_time_spread": spread,
         "config": {"workload": cfg.describe(), "flop_convention": "4*B*H*Nq*Nk*D, halved when causal",
+                   "flops_exact_visible_pairs": 4.0 * cfg.D * cfg.visible_pairs(),
                    "accumulate": "fp32", "inputs": "N(0,1) numpy PCG64 seeds %s, resident in HBM" % (cfg.seeds,),
                    "note": "Q,K,V,O of this workload (64 MiB) fit in the 256 MiB Infinity Cache"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -341,6 +374,22 @@ def main():
                                "kind": "oracle", "seconds": round(dt, 3),
                                "sample": f"all {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name}, "
                                          f"{passes} full pass(es), fp64"}
+        # the timed output against the oracle (whole workload), and against the oracle rounded to the output
+        # format, so that a miss by one rounding step can be told from a wrong result
+        o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
+        to, tl = outputs
+        o = I.bits_to_f64(to.cpu().numpy().view(np.uint16), cfg.dtype)
+        lse = tl.cpu().numpy().astype(np.float64)
+        err = np.abs(o - o_ref)
+        o_ref_rounded = I.bits_to_f64(I.f32_to_bits(o_ref.astype(np.float32), cfg.dtype), cfg.dtype)
+        worst = np.unravel_index(int(np.argmax(err)), err.shape)
+        fin = np.isfinite(lse_ref)
+        out["parity"] = {"against": "fp64 oracle, every element of the timed output",
+                         "o_max_abs": float(err.max()), "o_mean_abs": float(err.mean()),
+                         "lse_max_abs": float(np.abs(lse[fin] - lse_ref[fin]).max()),
+                         "o_max_abs_vs_oracle_rounded_to_dtype": float(np.abs(o - o_ref_rounded).max()),
+                         "elements_over_1e-2": int((err > 1e-2).sum()), "worst_element_bhid": [int(x) for x in worst],
+                         "tolerance": {"o_max_abs": 1e-2, "o_mean_abs": 1e-3, "lse_abs": 1e-3}}
 
     if not args.no_extra:
         extra = {}

@@ -245,6 +245,16 @@ int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row
 int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int wg_row_first, int wg_row_last,
                          int row_first, int row_last, int *first, int *count);
 
+/*
+ * fa_mfma_probe -- measurement aid: enqueues a kernel that issues nothing but independent
+ * v_mfma_f32_32x32x16 instructions of `dtype` (256 workgroups of 8 waves, `iters` x 4 instructions
+ * per wave) and reports the floating-point operations it performs in *flops (HOST pointer).  Timed
+ * by the caller, it gives the matrix throughput the chip sustains under its power limit -- the
+ * practical ceiling to quote beside the nominal peak.  `scratch`: DEVICE pointer to one float
+ * (never written in practice).  1 <= iters <= 2^24.
+ */
+int fa_mfma_probe(int dtype, int iters, float *scratch, long long *flops, void *stream);
+
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);
 

@@ -35,7 +35,7 @@ FA_MODE_WIDE_FOLD = 2
 # every symbol include/fa.h declares
 EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
            "fa_attn_linear", "fa_mask_tile_class",
-           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_strerror", "fa_version", "fa_last_hip_error")
+           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_mfma_probe", "fa_strerror", "fa_version", "fa_last_hip_error")
 
 _lib = None
 
@@ -101,6 +101,8 @@ def load() -> ctypes.CDLL:
         lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ip, ip]
         lib.fa_mask_interior_run.restype = ctypes.c_int
         lib.fa_mask_interior_run.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 7 + [ip, ip]
+        lib.fa_mfma_probe.restype = ctypes.c_int
+        lib.fa_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_longlong), vp]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -245,6 +247,15 @@ def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_r
     if rc != FA_OK:
         raise FaError(rc)
     return first.value, count.value
+
+
+def fa_mfma_probe(dtype, iters, scratch, stream=0) -> int:
+    """fa_mfma_probe of include/fa.h: enqueue the matrix-only kernel, return the flop it performs."""
+    flops = ctypes.c_longlong()
+    rc = load().fa_mfma_probe(int(dtype), int(iters), _addr(scratch), ctypes.byref(flops), _addr(stream))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return flops.value
 
 
 def fa_strerror(code: int) -> str:

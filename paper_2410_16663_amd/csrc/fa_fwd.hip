@@ -1136,6 +1136,30 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
         }
 }
 
+// ---- ceiling probe: nothing but independent matrix instructions, two waves per SIMD on every compute unit.
+// What this reaches is what the chip sustains under its power limit with the matrix pipes saturated and nothing
+// else going on -- the practical ceiling beside the nominal peak.  Four accumulators per wave keep the pipe fed.
+template <int DT>
+__global__ __launch_bounds__(512, 1) void fa_mfma_probe_kernel(float *out, int iters) {
+    s16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (short)(0x3c00 + ((threadIdx.x + i) & 7));   // small finite values in either format
+        b[i] = (short)(0x3800 + ((threadIdx.x + 3 * i) & 7));
+    }
+    f32x16 c0 = (f32x16)(0.f), c1 = c0, c2 = c0, c3 = c0;
+    for (int it = 0; it < iters; ++it) {
+        c0 = mfma32<DT>(a, b, c0);
+        c1 = mfma32<DT>(a, b, c1);
+        c2 = mfma32<DT>(a, b, c2);
+        c3 = mfma32<DT>(a, b, c3);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s == 12345.678f) out[0] = s;                        // never true: keeps the loop alive
+}
+
 // Merge of the split-KV partial results (the same merge the split mode does between its two
 // wave groups): with M = max_s m_s, L = sum_s l_s 2^(m_s - M), the row is
 // o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
@@ -1643,6 +1667,23 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
     const Run r = interior_run(row_tiles(g, row_first, row_last), tile_sequence(g, wg_row_first, wg_row_last), Nk);
     *first = r.first;
     *count = r.count;
+    return FA_OK;
+}
+
+int fa_mfma_probe(int dtype, int iters, float *scratch, long long *flops, void *stream) {
+    if (!scratch || !flops) return FA_ERR_NULL;
+    if (dtype != FA_DTYPE_F16 && dtype != FA_DTYPE_BF16) return FA_ERR_DTYPE;
+    if (iters <= 0 || iters > (1 << 24)) return FA_ERR_SHAPE;
+    if ((uintptr_t)scratch & 3) return FA_ERR_ALIGN;
+    const int grid = 256;                                   // one workgroup of 8 waves per compute unit
+    if (dtype == FA_DTYPE_F16) hipLaunchKernelGGL((fa_mfma_probe_kernel<0>), dim3(grid), dim3(512), 0, (hipStream_t)stream, scratch, iters);
+    else hipLaunchKernelGGL((fa_mfma_probe_kernel<1>), dim3(grid), dim3(512), 0, (hipStream_t)stream, scratch, iters);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return FA_ERR_LAUNCH;
+    }
+    *flops = (long long)grid * 8 * iters * 4 * (2LL * 32 * 32 * 16);
     return FA_OK;
 }
 

@@ -124,6 +124,17 @@ def test_attn_linear_argument_errors_come_back_before_any_launch(lib, change, co
     assert e.value.code == code
 
 
+def test_probe_argument_errors(lib):
+    import ctypes
+    f = ctypes.c_longlong()
+    L = fa.load()
+    assert L.fa_mfma_probe(0, 10, None, ctypes.byref(f), None) == fa.FA_ERR_NULL
+    assert L.fa_mfma_probe(0, 10, 0x1000, None, None) == fa.FA_ERR_NULL
+    assert L.fa_mfma_probe(2, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_DTYPE
+    assert L.fa_mfma_probe(0, 0, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
+    assert L.fa_mfma_probe(0, 10, 0x1002, ctypes.byref(f), None) == fa.FA_ERR_ALIGN
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(fa, "_lib", None)
     monkeypatch.setattr(fa, "LIB_PATH", str(tmp_path / "libfa.so"))
@@ -245,8 +256,9 @@ def test_build_report_shows_register_only_kernels():
     from paper_2410_16663_amd import build
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
-    # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile heights
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8
+    # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
+    # heights; matrix-only probe: 2 dtypes
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 2
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name
