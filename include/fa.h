@@ -228,8 +228,10 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
  *   FA_TILE_SKIP (certainly nothing visible), FA_TILE_FULL (certainly everything visible, and all
  *   64 keys exist), FA_TILE_PARTIAL (anything else), or a negative FA_ERR_* code.
  * fa_mask_tile_walk: the 64-key tiles a workgroup owning rows row_first..row_last visits, in
- *   order: tiles 0 .. *prefix_tiles-1, then *count - *prefix_tiles consecutive tiles starting at
- *   *window_first_tile.  Every tile holding a key visible to one of the rows is among them.
+ *   order: tiles 0 .. *prefix_tiles-1, then the cw = *count - *prefix_tiles consecutive tiles from
+ *   *window_first_tile on, starting with tile *window_first_tile + *window_rotation and wrapping
+ *   around (so that co-resident workgroups with shifted windows read the same tile at the same
+ *   time).  Every tile holding a key visible to one of the rows is among them.
  * fa_mask_interior_run: within the walk of the workgroup owning rows wg_row_first..wg_row_last, the
  *   positions [*first, *first + *count) that the wave owning rows row_first..row_last processes
  *   without any check: each of those tiles is FA_TILE_FULL for the wave and the tile at the next
@@ -241,7 +243,7 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
 int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk,
                        int row_first, int row_last, int key_first);
 int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
-                      int *prefix_tiles, int *window_first_tile, int *count);
+                      int *prefix_tiles, int *window_first_tile, int *count, int *window_rotation);
 int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int wg_row_first, int wg_row_last,
                          int row_first, int row_last, int *first, int *count);
 

@@ -98,7 +98,7 @@ def load() -> ctypes.CDLL:
         lib.fa_mask_tile_class.restype = ctypes.c_int
         lib.fa_mask_tile_class.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 6
         lib.fa_mask_tile_walk.restype = ctypes.c_int
-        lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ip, ip]
+        lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ip, ip, ip]
         lib.fa_mask_interior_run.restype = ctypes.c_int
         lib.fa_mask_interior_run.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 7 + [ip, ip]
         lib.fa_mfma_probe.restype = ctypes.c_int
@@ -229,12 +229,13 @@ def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last,
 def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last):
     """fa_mask_tile_walk of include/fa.h (host only): the list of tile indices, in the order walked."""
     m = _mask(left, right, prefix, None)
-    np_, base, count = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    np_, base, count, rot = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     rc = load().fa_mask_tile_walk(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last),
-                                  ctypes.byref(np_), ctypes.byref(base), ctypes.byref(count))
+                                  ctypes.byref(np_), ctypes.byref(base), ctypes.byref(count), ctypes.byref(rot))
     if rc != FA_OK:
         raise FaError(rc)
-    return list(range(np_.value)) + [base.value + i for i in range(count.value - np_.value)]
+    cw = count.value - np_.value
+    return list(range(np_.value)) + [base.value + (i + rot.value) % cw for i in range(cw)]
 
 
 def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_row_last, row_first, row_last):

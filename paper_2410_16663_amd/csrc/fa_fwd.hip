@@ -133,21 +133,37 @@ __host__ __device__ inline int tile_class(const RowTiles &w, int t) {
     return TILE_PARTIAL;
 }
 
-// The tiles a workgroup owning rows R0..R1 walks: the prefix tiles 0 .. np-1, then `count - np`
-// consecutive tiles from `base` on (the rows' window); when the two runs touch or overlap they are
-// one run from tile 0.  Position j of the walk is tile (j < np ? j : base + j - np).
+// The tiles a workgroup owning rows R0..R1 walks: the prefix tiles 0 .. np-1, then the cw = count - np
+// consecutive tiles base .. base+cw-1 that the rows' windows touch; when the two runs touch or overlap
+// they are one run from tile 0.  A window run that does not start at tile 0 is walked ROTATED: it starts
+// at tile base + rot and wraps around, with rot chosen so that the tile at window position i is
+// congruent to i modulo cw.  Neighbouring query blocks' windows are a few tiles apart; walked in
+// ascending order they would read the same tile a few iterations apart, and the co-resident
+// workgroups of a head would keep that head's whole K/V cycling through the L2; rotated, they read
+// the same tile in the same iteration.  (The order of the tiles does not matter to the result.)  Runs
+// shorter than 32 tiles are left in order: their footprint is small anyway, and the wrap cuts the
+// check-free run in two, of which only the longer is used.
+// Position j of the walk is tile (j < np ? j : base + ((j - np + rot) mod cw)).
 struct TileSeq {
-    int np, base, count;
+    int np, base, count, rot;
+    __host__ __device__ int tile(int j) const {
+        if (j < np) return j;
+        int i = j - np + rot;
+        const int cw = count - np;
+        if (i >= cw) i -= cw;
+        return base + i;
+    }
 };
 __host__ __device__ inline TileSeq tile_sequence(const MaskGeom &g, int R0, int R1) {
     constexpr int BNK = 64;
     const int p_t = (g.pfx + BNK - 1) / BNK;
     const int lo_key = max(0, R0 + g.off - g.left);
     const int hi_key = min(g.klen - 1, R1 + g.off + g.right);
-    if (hi_key < lo_key) return {p_t, 0, p_t};
+    if (hi_key < lo_key) return {p_t, 0, p_t, 0};
     const int w_lo = lo_key / BNK, w_hi = hi_key / BNK;
-    if (w_lo <= p_t) return {0, 0, max(p_t, w_hi + 1)};
-    return {p_t, w_lo, p_t + (w_hi - w_lo + 1)};
+    if (w_lo <= p_t) return {0, 0, max(p_t, w_hi + 1), 0};
+    const int cw = w_hi - w_lo + 1;
+    return {p_t, w_lo, p_t + cw, cw >= 32 ? (cw - w_lo % cw) % cw : 0};
 }
 
 // Folded row assignment (causal, few rounds of workgroups; kernel variant PAIR).  A head's rows are cut
@@ -174,10 +190,28 @@ struct Run {
 };
 __host__ __device__ inline Run interior_run(const RowTiles &w, const TileSeq &sq, int Nk) {
     const int phys = Nk / 64 - 2;                     // last tile t such that tile t+1 is wholly inside K/V
-    // window candidate, as tiles t0..t1 inclusive, restricted to the window part of the walk
-    int t0 = max(w.all_lo, sq.np > 0 ? sq.base : 0);
-    int t1 = min(min(w.all_hi, w.exist_all - 1), phys);
-    int a0 = t0 - sq.base + sq.np, a1 = t1 - sq.base + sq.np + 1;   // positions [a0, a1)
+    const int cw = sq.count - sq.np;                  // tiles of the window part
+    // window candidate: tiles f0..f1 inclusive, inside the window part of the walk
+    const int f0 = max(w.all_lo, sq.np > 0 ? sq.base : 0);
+    const int f1 = min(min(w.all_hi, w.exist_all - 1), min(phys, sq.base + cw - 1));
+    int a0 = 0, a1 = 0;                               // their positions [a0, a1)
+    if (f1 >= f0) {
+        const int ts = sq.base + sq.rot;              // the tile the window part starts with
+        // tiles ts .. come first, in order; tiles base .. ts-1 follow after the wrap, in order
+        const int hi0 = max(f0, ts), lo1 = min(f1, ts - 1);
+        const int len_hi = f1 - hi0 + 1, len_lo = lo1 - f0 + 1;
+        const int pos_hi = sq.np + hi0 - ts, pos_lo = sq.np + (cw - sq.rot) + (f0 - sq.base);
+        if (len_hi > 0 && len_lo > 0 && f1 == sq.base + cw - 1 && f0 == sq.base) {
+            a0 = pos_hi;                              // the two pieces meet at the wrap: one run
+            a1 = pos_hi + len_hi + len_lo;
+        } else if (len_hi >= len_lo) {
+            a0 = pos_hi;
+            a1 = pos_hi + max(len_hi, 0);
+        } else {
+            a0 = pos_lo;
+            a1 = pos_lo + len_lo;
+        }
+    }
     a1 = min(a1, sq.count - 1);
     // prefix candidate: positions = tiles 0 .. p1-1
     int p1 = min(min(w.pfx_all, w.exist_all), phys + 1);
@@ -366,7 +400,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     if constexpr (SPLITKV) n_act = max(n_act - t_lo, 0);
     // descriptor masks: the workgroup's walk and this wave's rows
     MaskGeom mg = {off, 0, 0, 0, Nk};
-    TileSeq seq = {0, 0, 0};
+    TileSeq seq = {0, 0, 0, 0};
     RowTiles wt = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (GENMASK) {
         int klen = Nk;
@@ -382,7 +416,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // paired fold: the tile this wave works on in the current iteration, and how many tiles its block needs
     int pair_tile = 0, pair_need = 0;
     auto tile_of = [&](int j) __attribute__((always_inline)) -> int {
-        if constexpr (GENMASK) return j < seq.np ? j : seq.base + (j - seq.np);
+        if constexpr (GENMASK) return seq.tile(j);
         if constexpr (PAIR) return pair_tile;
         return t_lo + TSTEP * j + grp;
     };
@@ -1643,8 +1677,8 @@ int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int ro
 }
 
 int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
-                      int *prefix_tiles, int *window_first_tile, int *count) {
-    if (!prefix_tiles || !window_first_tile || !count) return FA_ERR_NULL;
+                      int *prefix_tiles, int *window_first_tile, int *count, int *window_rotation) {
+    if (!prefix_tiles || !window_first_tile || !count || !window_rotation) return FA_ERR_NULL;
     MaskGeom g;
     const int rc = mask_geometry(mask, kv_len, Nq, Nk, &g);
     if (rc != FA_OK) return rc;
@@ -1653,6 +1687,7 @@ int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row
     *prefix_tiles = sq.np;
     *window_first_tile = sq.base;
     *count = sq.count;
+    *window_rotation = sq.rot;
     return FA_OK;
 }
 

@@ -76,6 +76,12 @@ def test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left
             # the walk is the prefix tiles plus one contiguous run: at most the gap-free hull of what is needed
             if needed and prefix == 0:
                 assert set(walk) == set(range(min(needed), max(needed) + 1))
+                # ... walked in ascending order from tile 0, or rotated so that position i holds a tile
+                # congruent to i modulo the length of the run
+                if min(walk) == 0 or len(walk) < 32:
+                    assert walk == sorted(walk)
+                else:
+                    assert all(t % len(walk) == i for i, t in enumerate(walk))
 
 
 @pytest.mark.parametrize("Nq,Nk", SHAPES + [(1024, 1024), (300, 1100)])
@@ -106,6 +112,25 @@ def test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, pref
                     assert count >= best - 3, (klen, R0, r0, first, count, best)
 
 
+BIG_SHAPES = [(3000, 3000), (2500, 4100), (4100, 2500)]
+BIG_DESCRIPTORS = [(2200, 0, 0), (2048, 300, 0), (2300, 0, 128), (2100, 2100, 0), (2500, 0, 700)]
+
+
+@pytest.mark.parametrize("Nq,Nk", BIG_SHAPES)
+@pytest.mark.parametrize("left,right,prefix", BIG_DESCRIPTORS)
+def test_long_windows_are_walked_rotated_and_still_cover_everything(lib, left, right, prefix, Nq, Nk):
+    """Window runs of 32 tiles and more: the rotated walk, its classification and its check-free run."""
+    test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk)
+    test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk)
+    rotated = 0
+    for R0 in range(0, Nq, 256):
+        R1 = min(R0 + 255, Nq - 1)
+        walk = fa.fa_mask_tile_walk(left, right, prefix, Nk, Nq, Nk, R0, R1)
+        rotated += walk != sorted(walk)
+    if prefix < 512 and Nk >= Nq:                        # (a long prefix or few keys merge the window run into one from tile 0)
+        assert rotated > 0                               # the case is exercised at all
+
+
 def test_causal_walk_matches_the_causal_plan(lib):
     """(-1, 0) walks what fa_fwd's wide mode walks for the same rows."""
     Nq = Nk = 2048
@@ -127,7 +152,11 @@ def test_sliding_window_walk_is_short(lib):
     for R0 in (0, 8192, N - 256):
         walk = fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, R0, R0 + 255)
         lo, hi = max(0, R0 - (W - 1)) // BN, (R0 + 255) // BN
-        assert walk == list(range(lo, hi + 1))
+        assert sorted(walk) == list(range(lo, hi + 1))
+    # neighbouring query blocks read their common tiles at the same positions of their walks
+    w1 = fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, 8192, 8192 + 255)
+    w2 = fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, 8192 + 256, 8192 + 511)
+    assert len(w1) == len(w2) and sum(a == b for a, b in zip(w1, w2)) == len(w1) - 4
     assert len(fa.fa_mask_tile_walk(W - 1, 0, 0, N, N, N, 8192, 8192 + 255)) == (W + 256) // BN
 
 
@@ -161,3 +190,7 @@ def test_null_descriptor_and_bad_host_queries(lib):
         fa.fa_mask_tile_class(-1, 0, 0, 8, 8, 128, 0, 7, 32)     # not a tile boundary
     with pytest.raises(fa.FaError):
         fa.fa_mask_tile_walk(-1, 0, -2, 8, 8, 8, 0, 7)
+    import ctypes
+    m = fa.FaMask(-1, 0, 0, None)
+    i3 = [ctypes.c_int() for _ in range(3)]
+    assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, *[ctypes.byref(x) for x in i3], None) == fa.FA_ERR_NULL

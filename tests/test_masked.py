@@ -47,6 +47,23 @@ def test_descriptor_masks_elementwise(oracle, shape, mask, dtype):
     assert (I.bits_to_f64(o, dtype)[empty] == 0).all()
 
 
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", [(2200, 0, 0), (2048, 300, 0), (2100, 0, 128), (2300, 2300, 0)])
+@pytest.mark.parametrize("shape", [(1, 2, 3000, 3000, 128), (1, 1, 2500, 4100, 64)])
+def test_long_windows_walked_in_rotated_order(oracle, shape, mask, dtype):
+    """Window runs of 32 tiles and more are walked rotated (so that neighbouring query blocks read the same tile
+    at the same time): the wrap falls in the middle of a wave's fully visible tiles."""
+    B, H, Nq, Nk, D = shape
+    left, right, prefix = mask
+    print(f"case masked rotated shape={shape} mask={mask} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, mask, dtype)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} {mask} dt={dtype}")
+
+
 def test_causal_and_unmasked_descriptors_equal_fa_fwd_bit_for_bit(monkeypatch):
     """(-1, 0) and (-1, -1) walk the same tiles with the same arithmetic as fa_fwd's wide mode."""
     print("case masked vs fa_fwd", flush=True)
