@@ -166,7 +166,9 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
  * Calls for different blocks are independent.  Error behaviour as for fa_fwd.  The GEMM's
  * workgroup tile is 256 tokens x 256 outputs when that still gives each of the 256 compute units
  * a workgroup (B * ceil(row_count/256) * N/256 >= 256), else 128 x 256; the environment variable
- * FA_LINEAR_TILE=128|256 overrides (tests, tuning).
+ * FA_LINEAR_TILE=128|256 overrides (tests, tuning).  The tiles are dealt to the XCDs in panels of
+ * a few row tiles so that each L2 fetches about as many bytes of o as of w; FA_LINEAR_PANEL=<row
+ * tiles per panel> overrides that too (the order changes no result).
  *
  * fa_attn_linear -- every block in order on one stream: blocks of rows_per_block rows, the first
  * one half that size (nothing can overlap with the first block); rows_per_block <= 0: one block.

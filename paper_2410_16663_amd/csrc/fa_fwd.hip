@@ -1020,6 +1020,7 @@ struct LinParams {
     int mt_per_b;          // 128-row tiles per batch entry
     int n_tiles;           // 256-wide tiles of N
     int ntile_total, per_xcd;
+    int panel;             // row tiles per panel of the tile order
 };
 
 template <int DT, int D, int BM>
@@ -1043,12 +1044,17 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
     const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, h = lane >> 5;
 
-    // workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of the tile list,
-    // ordered output-tile-major, so the workgroups sharing an L2 use the same few column slices of w
+    // workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of the tile list.
+    // The list goes panel of `panel` row tiles by panel, within a panel column slice by column slice, so
+    // that the workgroups sharing an L2 cover a block of about as many bytes of o rows as of w columns
+    // (every L2 has to fetch the rows and the columns of its block once)
     const int wi = (blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
     if (wi >= p.ntile_total) return;
     const int m_tiles = p.ntile_total / p.n_tiles;
-    const int nt = wi / m_tiles, mt = wi % m_tiles;
+    const int panel_tiles = p.panel * p.n_tiles;
+    const int pn = wi / panel_tiles, rem = wi - pn * panel_tiles;
+    const int panel_rows = min(p.panel, m_tiles - pn * p.panel);
+    const int nt = rem / panel_rows, mt = pn * p.panel + rem % panel_rows;
     const int b = mt / p.mt_per_b;
     const int r0 = (mt % p.mt_per_b) * BM;        // first row of the tile within the block
     const int n0 = nt * BNO;
@@ -1388,6 +1394,18 @@ hipError_t launch_linear(const LinParams &p, int BM, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// Row tiles per panel of the projection's tile order.  The c = min(per_xcd, 32) workgroups an XCD runs at a
+// time (one per compute unit) are consecutive tiles of its run: R row tiles by c / R column slices, for which
+// its L2 fetches R * BM rows of o and (c / R) * 256 columns of w, each K elements long: least for
+// R = sqrt(c * 256 / BM).  Measured: 4% on launches of several rounds, nothing on single-round ones.
+int linear_panel(int per_xcd, int BM, int m_tiles) {
+    const int c = per_xcd < 32 ? per_xcd : 32;
+    int R = 1;
+    while ((R + 1) * (R + 1) * BM <= c * 256) ++R;
+    if (R > m_tiles) R = m_tiles;
+    return R < 1 ? 1 : R;
+}
+
 // The parameter block every entry point starts from: one launch over the whole of q (no row range,
 // no split, no descriptor mask).
 FaParams base_params(const void *q, const void *k, const void *v, void *o, float *lse, int H, int Nq, int Nk,
@@ -1636,6 +1654,11 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
         if (tiles > 0x7ffffff0LL) return FA_ERR_SHAPE;
         lp.ntile_total = (int)tiles;
         lp.per_xcd = (int)((tiles + 7) / 8);
+        lp.panel = linear_panel(lp.per_xcd, BM, B * lp.mt_per_b);
+        if (const char *env = getenv("FA_LINEAR_PANEL")) {   // tests, tuning
+            const int v = atoi(env);
+            if (v >= 1) lp.panel = v < B * lp.mt_per_b ? v : B * lp.mt_per_b;
+        }
         hipError_t e;
         switch ((dtype << 1) | (D == 128)) {
             case 0: e = launch_linear<0, 64>(lp, BM, st); break;

@@ -86,6 +86,26 @@ def test_blocks_are_independent_and_touch_only_their_rows(oracle, monkeypatch, m
     assert np.isnan(y[:, ~done]).all() and np.isnan(lse[:, :, ~done]).all() and (o[:, :, ~done] == 0x7E00).all()
 
 
+def test_tile_order_changes_no_bit(monkeypatch, tile):
+    """The order in which the projection's tiles are dealt to the compute units (panels of a few row tiles,
+    FA_LINEAR_PANEL of include/fa.h) decides which workgroup computes a tile, never what it computes: every
+    panel height, also ones that do not divide the number of row tiles, gives the same y bit for bit."""
+    print(f"case attn_linear tile order tile={tile}", flush=True)
+    rng = np.random.default_rng(603)
+    B, H, Nq, Nk, D, N = 3, 2, 900, 900, 64, 1024
+    q, k, v, w = make(rng, B, H, Nq, Nk, D, N, I.BF16)
+    results = []
+    for panel in ("1", "3", "4", "7", "1000"):
+        monkeypatch.setenv("FA_LINEAR_PANEL", panel)
+        o, lse, y = run_attn_linear(q, k, v, w, 0.12, True, I.BF16)
+        assert np.isfinite(y).all()
+        results.append(y)
+    monkeypatch.delenv("FA_LINEAR_PANEL")
+    o, lse, y = run_attn_linear(q, k, v, w, 0.12, True, I.BF16)
+    for r in results:
+        assert np.array_equal(r, y)
+
+
 def test_one_block_gives_fa_fwd_bit_for_bit_and_exact_projections():
     """The whole problem as one block runs the same attention launch as fa_fwd; with w = identity columns the
     projection returns o itself (products with 1 and 0, fp32 sums of one term)."""
