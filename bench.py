@@ -158,7 +158,8 @@ def decode_entry(I, torch, fa, steps, warmup):
             "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic("splitkv_DEC"),
-                         "kernel": "fa_fwd_kernel (wide, split-KV) + fa_combine_kernel",
+                         "kernel": ("fa_decode_kernel" if plan.streaming else "fa_fwd_kernel (wide, split-KV)")
+                                   + " + fa_combine_kernel",
                          "bytes_per_call": kv_bytes}}
 
 

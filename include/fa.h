@@ -110,10 +110,14 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
  * workgroup each; every run leaves an unnormalised partial result (accumulator, exponent
  * reference, row sum -- the running quantities of appendix A) in `workspace`, and a second
  * kernel merges them: lse = logsumexp over runs, o = sum_runs exp(lse_run - lse) o_run.
- * Bound by reading K and V once from HBM.
+ * Bound by reading K and V once from HBM.  Nq = 1, the decoding step proper, runs a kernel of its
+ * own that streams K and V through registers (one multiply-add per element leaves the matrix
+ * cores nothing to reuse) and keeps the probabilities in fp32; the environment variable
+ * FA_DECODE=mfma sends it through the tile kernel instead (tests, tuning).
  *
  *   nsplit          : > 0: number of runs (clamped to the number of 64-key tiles, at most 1024);
- *                     <= 0: the library picks (256 workgroups at D = 128, 512 at D = 64, runs of >= 4 tiles)
+ *                     <= 0: the library picks (256 workgroups at D = 128 and for a single query,
+ *                     512 at D = 64 otherwise; runs of >= 4 tiles)
  *   workspace       : DEVICE pointer, 16-byte aligned, caller-owned scratch of at least
  *                     fa_fwd_splitkv_plan(...).workspace_bytes; contents on entry are ignored,
  *                     contents on return are unspecified; must not alias any other argument
@@ -130,10 +134,11 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
 
 typedef struct fa_splitkv_plan {
     int nsplit;                 /* runs actually used */
-    int grid_x, grid_y;         /* first kernel: work items (rounded up to a multiple of 8) x runs */
+    int grid_x, grid_y;         /* first kernel: work items (tile kernel: rounded up to a multiple of 8) x runs */
     int combine_grid;           /* second kernel: blocks of 256 threads */
     long long work_items;       /* B * H * ceil(Nq / 256) */
     long long workspace_bytes;  /* nsplit * B * H * Nq * (D + 2) * 4 */
+    int streaming;              /* 1: the register-streaming kernel of the single-query case, 0: the tile kernel */
 } fa_splitkv_plan_t;
 
 /*

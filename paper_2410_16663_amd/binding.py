@@ -52,7 +52,7 @@ class FaSplitKvPlan(ctypes.Structure):
     """fa_splitkv_plan_t of include/fa.h."""
     _fields_ = [("nsplit", ctypes.c_int), ("grid_x", ctypes.c_int), ("grid_y", ctypes.c_int),
                 ("combine_grid", ctypes.c_int), ("work_items", ctypes.c_longlong),
-                ("workspace_bytes", ctypes.c_longlong)]
+                ("workspace_bytes", ctypes.c_longlong), ("streaming", ctypes.c_int)]
 
 
 class FaMask(ctypes.Structure):

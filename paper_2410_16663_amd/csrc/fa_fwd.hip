@@ -300,12 +300,18 @@ __device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char 
     return (const unsigned char *)(uintptr_t)(lo | (hi << 32));
 }
 
-template <int IMM>
+template <int IMM, bool NT = false>
 __device__ __forceinline__ void dma16_to_lds(const void *gbase, unsigned voff, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(gbase), "n"(IMM)
-                 : "memory", "m0");
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3 nt"
+                     :
+                     : "s"(lds_addr), "v"(voff), "s"(gbase), "n"(IMM)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+                     :
+                     : "s"(lds_addr), "v"(voff), "s"(gbase), "n"(IMM)
+                     : "memory", "m0");
 }
 
 // WIDE = false: the two groups of four waves work on the SAME 128 query rows and take
@@ -345,6 +351,10 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
     // issue their loads first thing in an iteration instead of between the two matrix clusters
     constexpr int NSTAGE = SPLITKV ? 3 : 2;
     constexpr bool LOADS_FIRST = SPLITKV;
+    // split-KV streams K and V once (few query blocks per head): its loads carry the non-temporal hint, worth
+    // 6.6-7.0 instead of 5.6-6.0 TB/s there; on the other kernels, whose workgroups share K/V tiles through L2,
+    // the same hint costs 3-15%
+    constexpr bool KV_NT = SPLITKV;
     constexpr int GROUPB = 2 * NSTAGE * TILEB;    // one set of buffers: K0 .. K(NSTAGE-1) V0 .. V(NSTAGE-1)
     constexpr int NSETS = (WIDE && !PAIR) ? 1 : 2;   // split mode: one set per group; paired fold: one per tile of an iteration
 
@@ -482,7 +492,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
             for (int n = 0; n < NI; ++n) {
                 const int i = wq + n * NWL;
                 if (NINSTR % NWL == 0 || i < NINSTR)
-                    dma16_to_lds<0>(uniform_ptr(gb + (size_t)t * TILEB + n * NWL * 1024), (unsigned)voff,
+                    dma16_to_lds<0, KV_NT>(uniform_ptr(gb + (size_t)t * TILEB + n * NWL * 1024), (unsigned)voff,
                                     lds_base + lds_off + i * 1024);
             }
         } else {
@@ -491,7 +501,7 @@ __global__ __launch_bounds__(512, 2) void fa_fwd_kernel(const FaParams p) {
                 const int i = wq + n * NWL;
                 if (NINSTR % NWL == 0 || i < NINSTR) {
                     const int key = min(t * BN + ld_row0 + n * NWL * RPI, Nk - 1);
-                    dma16_to_lds<0>(uniform_ptr(gb), (unsigned)(key * ROWB + voff - ld_row0 * ROWB),
+                    dma16_to_lds<0, KV_NT>(uniform_ptr(gb), (unsigned)(key * ROWB + voff - ld_row0 * ROWB),
                                     lds_base + lds_off + i * 1024);
                 }
             }
@@ -1205,6 +1215,184 @@ __global__ __launch_bounds__(512, 1) void fa_mfma_probe_kernel(float *out, int i
 // o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
 // left m = -1e30, l = 0, acc = 0 and drops out; a row with no visible key at all gets o = 0,
 // lse = -inf.  One thread per (row, 4 consecutive d).
+// ---- decoding step (appendix C's decoding equations: one query row per head against the whole cache).
+// With a single query there is nothing for the matrix cores to reuse: every byte of K and V meets one
+// multiply-add, the bound is HBM, and the tile machinery of fa_fwd_kernel (LDS staging, barriers, 31 idle
+// rows of every matrix instruction) only stands between the memory system and the arithmetic.  This kernel
+// streams K and V through registers instead.  blockIdx.x = (batch, head), blockIdx.y = one of p.nsplit runs
+// of keys (the same runs of 64-key tiles as the split-KV kernel's); four waves take the run's blocks of KB
+// keys in turn.  A load instruction fetches 64 x 16 bytes = RPI whole rows, LPR = D/8 lanes per row; the LPR
+// lanes of a row each multiply their 8 channels by the matching channels of q (held in registers, scale
+// folded in) and add up across the row with DPP moves; each of the RPI lane groups keeps its own running
+// reference, sum and 8-channel slice of the output for the rows it sees, in fp32 throughout (the
+// probabilities are never rounded to 16 bits here).  The 4 x RPI partial states of the workgroup are merged
+// through LDS and written to the split-KV workspace in the layout fa_combine_kernel reads.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+// sum over the LPR (8 or 16) consecutive lanes that share a row; every one of them gets the total
+template <int LPR>
+__device__ __forceinline__ float row_lanes_sum(float x) {
+    x += dpp_move<0xB1>(x);              // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);              // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);             // row_half_mirror: lane i <-> 7 - i of each 8
+    if constexpr (LPR == 16) x += dpp_move<0x140>(x);   // row_mirror: lane i <-> 15 - i of each 16
+    return x;
+}
+// two 16-bit values of the storage type packed in 32 bits -> two fp32 (exact)
+template <int DT>
+__device__ __forceinline__ f32x2 unpack2(unsigned u) {
+    if constexpr (DT == FA_DTYPE_F16) {
+        const f16x2 hh = __builtin_bit_cast(f16x2, u);
+        return f32x2{(float)hh[0], (float)hh[1]};
+    } else {
+        return f32x2{__builtin_bit_cast(float, u << 16), __builtin_bit_cast(float, u & 0xffff0000u)};
+    }
+}
+
+// 16 bytes that no other workgroup will ask for again: loaded with the non-temporal hint, so that the
+// stream does not displace anything in L2 or the Infinity Cache (measured: 6.7-7.0 TB/s instead of 5.9-6.0)
+__device__ __forceinline__ uint4 load16_streaming(const uint16_t *p) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 x = __builtin_nontemporal_load((const u32x4 *)p);
+    return uint4{x[0], x[1], x[2], x[3]};
+}
+constexpr int DECODE_WAVES = 4;
+template <int DT, int D>
+__global__ __launch_bounds__(DECODE_WAVES * 64) void fa_decode_kernel(const FaParams p) {
+    constexpr int LPR = D / 8;                    // lanes per K/V row (16 bytes each)
+    constexpr int RPI = 64 / LPR;                 // rows per load instruction
+    constexpr int NLD = 8;                        // load instructions per block and tensor
+    constexpr int KB = NLD * RPI;                 // keys per block
+    constexpr int NW = DECODE_WAVES;              // waves
+    constexpr int NG = NW * RPI;                  // lane groups, each with a partial state
+    __shared__ float sm_o[NG][D];
+    __shared__ float sm_ml[NG][2];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane / LPR, c = lane % LPR;
+    const int bh = blockIdx.x, sp = blockIdx.y;
+    const int Nk = p.Nk;
+    const int nt_all = (Nk + BN - 1) / BN;
+    const int k_lo = (int)((long long)sp * nt_all / p.nsplit) * BN;
+    const int k_hi = min(Nk, (int)((long long)(sp + 1) * nt_all / p.nsplit) * BN);
+
+    // this lane's 8 channels of q, times scale * log2(e): logits in base-2 units as in fa_fwd_kernel
+    const float cs = p.qmode == 0 ? p.c : (p.qmode == 1 ? -p.c : 0.f);
+    float qf[8];
+    {
+        const uint4 qq = *(const uint4 *)(p.q + (size_t)bh * D + c * 8);
+        const unsigned qw[4] = {qq.x, qq.y, qq.z, qq.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x2 f = unpack2<DT>(qw[j]);
+            qf[2 * j] = f[0] * cs;
+            qf[2 * j + 1] = f[1] * cs;
+        }
+    }
+    const uint16_t *kbase = p.k + (size_t)bh * Nk * D + c * 8;
+    const uint16_t *vbase = p.v + (size_t)bh * Nk * D + c * 8;
+
+    float m = -1e30f, l = 0.f, o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = 0.f;
+
+    // rows past the end of the run are fetched as its last row (and masked below)
+    auto load_block = [&](int key0, uint4 *kk, uint4 *vv) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            const int row = min(key0 + n * RPI + g, k_hi - 1);
+            kk[n] = load16_streaming(kbase + (size_t)row * D);
+        }
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            const int row = min(key0 + n * RPI + g, k_hi - 1);
+            vv[n] = load16_streaming(vbase + (size_t)row * D);
+        }
+    };
+    auto compute_block = [&](int key0, const uint4 *kk, const uint4 *vv) __attribute__((always_inline)) {
+        float t[NLD];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            const unsigned kw[4] = {kk[n].x, kk[n].y, kk[n].z, kk[n].w};
+            float a = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x2 f = unpack2<DT>(kw[j]);
+                a = __builtin_fmaf(qf[2 * j], f[0], a);
+                a = __builtin_fmaf(qf[2 * j + 1], f[1], a);
+            }
+            a = row_lanes_sum<LPR>(a);
+            t[n] = key0 + n * RPI + g < k_hi ? a : -INFINITY;
+            mx = fmaxf(mx, t[n]);
+        }
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        l *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] *= alpha;
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            const float pn = __builtin_amdgcn_exp2f(t[n] - m_new);
+            l += pn;
+            const unsigned vw[4] = {vv[n].x, vv[n].y, vv[n].z, vv[n].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x2 f = unpack2<DT>(vw[j]);
+                o[2 * j] = __builtin_fmaf(pn, f[0], o[2 * j]);
+                o[2 * j + 1] = __builtin_fmaf(pn, f[1], o[2 * j + 1]);
+            }
+        }
+        m = m_new;
+    };
+
+    // this wave's blocks: wave, wave + NW, ...; the next block's loads are in flight while one is worked on
+    const int nb = k_hi > k_lo ? (k_hi - k_lo + KB - 1) / KB : 0;
+    uint4 kb0[NLD], vb0[NLD], kb1[NLD], vb1[NLD];
+    if (wave < nb) load_block(k_lo + wave * KB, kb0, vb0);
+    for (int i = wave; i < nb; i += 2 * NW) {
+        const bool second = i + NW < nb;
+        if (second) load_block(k_lo + (i + NW) * KB, kb1, vb1);
+        compute_block(k_lo + i * KB, kb0, vb0);
+        if (second) {
+            if (i + 2 * NW < nb) load_block(k_lo + (i + 2 * NW) * KB, kb0, vb0);
+            compute_block(k_lo + (i + NW) * KB, kb1, vb1);
+        }
+    }
+
+    // ---- merge the workgroup's NG partial states
+    const int grp = wave * RPI + g;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm_o[grp][c * 8 + j] = o[j];
+    if (c == 0) {
+        sm_ml[grp][0] = m;
+        sm_ml[grp][1] = l;
+    }
+    __syncthreads();
+    if (tid < D) {
+        float M = -1e30f;
+#pragma unroll
+        for (int q = 0; q < NG; ++q) M = fmaxf(M, sm_ml[q][0]);
+        float L = 0.f, O = 0.f;
+#pragma unroll
+        for (int q = 0; q < NG; ++q) {
+            const float w = __builtin_amdgcn_exp2f(sm_ml[q][0] - M);
+            L += sm_ml[q][1] * w;
+            O += sm_o[q][tid] * w;
+        }
+        const size_t row = (size_t)sp * gridDim.x + bh;
+        p.part_o[row * D + tid] = O;
+        if (tid == 0) {
+            const float2 ml = {M, L};
+            *(float2 *)(p.part_ml + row * 2) = ml;
+        }
+    }
+}
+
 template <int DT, int D>
 __global__ __launch_bounds__(256) void fa_combine_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                                          uint16_t *__restrict__ o, float *__restrict__ lse, long long rows,
@@ -1253,6 +1441,17 @@ hipError_t launch_splitkv(const FaParams &p, int nwork_padded, long long rows, h
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr int RPB = 256 / (D / 4);            // rows per combine block
+    hipLaunchKernelGGL((fa_combine_kernel<DT, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream,
+                       p.part_o, p.part_ml, p.o, p.lse, rows, p.nsplit);
+    return hipGetLastError();
+}
+
+template <int DT, int D>
+hipError_t launch_decode(const FaParams &p, int heads, long long rows, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_decode_kernel<DT, D>), dim3(heads, p.nsplit), dim3(DECODE_WAVES * 64), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int RPB = 256 / (D / 4);
     hipLaunchKernelGGL((fa_combine_kernel<DT, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream,
                        p.part_o, p.part_ml, p.o, p.lse, rows, p.nsplit);
     return hipGetLastError();
@@ -1333,11 +1532,17 @@ long long tiles_walked(int mode, long long nqt, long long qt, int Nq, int Nk, in
 // D = 64, whose tiles are half the bytes (measured best: the path is bound by HBM, which that
 // many workgroups' loads in flight saturate, and every further run only adds its fixed cost
 // and its share of the merge), each run at least four tiles long.
+// The streaming kernel of the single-query case (fa_decode_kernel) does best with one four-wave workgroup
+// per compute unit as well (each wave keeps 32 KiB of loads in flight): more of them only shorten the
+// contiguous runs and add partial results to merge (measured: 512 workgroups 1-3% slower, 1024 5-10%).
 constexpr int SPLITKV_MAX = 1024;
-int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
+constexpr long long DECODE_WORKGROUPS = 256;
+int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in, bool streaming) {
     long long n = nsplit_in;
     if (n <= 0) {
-        const long long target = D == 128 ? 256 : 512;
+        long long target = streaming ? DECODE_WORKGROUPS : (D == 128 ? 256 : 512);
+        if (streaming)
+            if (const char *env = getenv("FA_DECODE_WORKGROUPS")) { const long long v = atoll(env); if (v >= 1) target = v; }
         n = (target + nwork - 1) / nwork;
         if (n > tiles_k / 4) n = tiles_k / 4;
     }
@@ -1345,6 +1550,13 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in) {
     if (n > SPLITKV_MAX) n = SPLITKV_MAX;
     if (n < 1) n = 1;
     return (int)n;
+}
+
+// One query row per head goes through the streaming kernel (FA_DECODE=mfma keeps the tile kernel: tests, tuning)
+bool use_streaming_decode(int Nq) {
+    if (Nq != 1) return false;
+    const char *env = getenv("FA_DECODE");
+    return !(env && !strcmp(env, "mfma"));
 }
 
 template <int DT, int D>
@@ -1514,10 +1726,12 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
     const long long nqt = ((long long)Nq + 255) / 256;
     const long long nwork = (long long)B * H * nqt;
     const long long tiles_k = ((long long)Nk + BN - 1) / BN;
-    const int ns = choose_nsplit(nwork, tiles_k, D, nsplit);
+    const bool streaming = use_streaming_decode(Nq);
+    const int ns = choose_nsplit(nwork, tiles_k, D, nsplit, streaming);
     const long long rows = (long long)B * H * Nq;
     plan->nsplit = ns;
-    plan->grid_x = (int)(((nwork + 7) / 8) * 8);
+    plan->streaming = streaming ? 1 : 0;
+    plan->grid_x = streaming ? (int)nwork : (int)(((nwork + 7) / 8) * 8);
     plan->grid_y = ns;
     plan->combine_grid = (int)((rows + (1024 / D) - 1) / (1024 / D));
     plan->work_items = nwork;
@@ -1547,6 +1761,20 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     hipStream_t st = (hipStream_t)stream;
 
     hipError_t e;
+    if (pl.streaming) {
+        // one query sees every key under the bottom-right-aligned causal mask: causal or not is the same
+        switch ((dtype << 1) | (D == 128)) {
+            case 0: e = launch_decode<0, 64>(p, pl.grid_x, rows, st); break;
+            case 1: e = launch_decode<0, 128>(p, pl.grid_x, rows, st); break;
+            case 2: e = launch_decode<1, 64>(p, pl.grid_x, rows, st); break;
+            default: e = launch_decode<1, 128>(p, pl.grid_x, rows, st); break;
+        }
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+        return FA_OK;
+    }
     const int key = (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
         case 0: e = launch_splitkv<0, 64, false>(p, pl.grid_x, rows, st); break;

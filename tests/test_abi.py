@@ -81,20 +81,30 @@ def test_splitkv_argument_errors_come_back_before_any_launch(lib, change, code):
     assert e.value.code == code
 
 
-def test_splitkv_plan(lib):
+@pytest.mark.parametrize("decode_kernel", ["stream", "mfma"])
+def test_splitkv_plan(lib, monkeypatch, decode_kernel):
+    """Nq = 1 goes to the streaming kernel (one workgroup per (batch, head) and run, no rounding of the grid)
+    unless FA_DECODE=mfma keeps it on the tile kernel; everything else is the tile kernel's either way."""
+    monkeypatch.setenv("FA_DECODE", decode_kernel)
+    stream = decode_kernel == "stream"
     # given nsplit: kept, clamped to the number of 64-key tiles
     p = fa.fa_fwd_splitkv_plan(2, 4, 1, 64 * 100, 128, 1, 0, 7)
-    assert (p.nsplit, p.grid_x, p.grid_y, p.work_items) == (7, 8, 7, 8)
+    assert (p.nsplit, p.grid_x, p.grid_y, p.work_items, p.streaming) == (7, 8, 7, 8, int(stream))
     assert p.workspace_bytes == 7 * 2 * 4 * 1 * (128 + 2) * 4
     assert p.combine_grid == 1                                   # 8 rows, 8 rows per block at D = 128
+    p = fa.fa_fwd_splitkv_plan(1, 3, 1, 64 * 100, 64, 0, 1, 2)
+    assert (p.grid_x, p.grid_y, p.streaming) == ((3, 2, 1) if stream else (8, 2, 0))
     assert fa.fa_fwd_splitkv_plan(1, 1, 1, 130, 64, 0, 0, 50).nsplit == 3
-    assert fa.fa_fwd_splitkv_plan(1, 1, 40, 130, 64, 0, 0, 1).combine_grid == 3   # 16 rows per block at D = 64
+    p = fa.fa_fwd_splitkv_plan(1, 1, 40, 130, 64, 0, 0, 1)
+    assert p.combine_grid == 3 and p.streaming == 0                               # 16 rows per block at D = 64
     # chosen: 256 workgroups, runs of at least four tiles, at least one run
     assert fa.fa_fwd_splitkv_plan(1, 32, 1, 32768, 128, 1, 1).nsplit == 8
     assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 128, 1, 1).nsplit == 1
     assert fa.fa_fwd_splitkv_plan(2, 24, 1, 32768, 128, 1, 1).nsplit == 6        # ceil(256 / 48)
     assert fa.fa_fwd_splitkv_plan(1, 8, 1, 2048, 128, 1, 1).nsplit == 8          # 32 tiles / 4
-    assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 64, 1, 1).nsplit == 2         # D = 64: 512 workgroups
+    # D = 64: 512 workgroups of the tile kernel (two fit a compute unit), 256 of the streaming kernel
+    assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 64, 1, 1).nsplit == (1 if stream else 2)
+    assert fa.fa_fwd_splitkv_plan(8, 32, 2, 32768, 64, 1, 1).nsplit == 2
     assert fa.fa_fwd_splitkv_plan(1, 1, 1, 100, 128, 1, 1).nsplit == 1
     assert fa.fa_fwd_splitkv_plan(64, 32, 300, 4096, 128, 1, 1).nsplit == 1      # enough work items already
     with pytest.raises(fa.FaError) as e:
@@ -257,8 +267,8 @@ def test_build_report_shows_register_only_kernels():
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
     # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
-    # heights; matrix-only probe: 2 dtypes
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 2
+    # heights; matrix-only probe: 2 dtypes; streaming decode: 2 dtypes x 2 head dims
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 2 + 4
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

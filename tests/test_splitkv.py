@@ -21,25 +21,35 @@ def rand_bits(rng, shape, dtype, mult=1.0):
 # B, H, Nq, Nk, D
 DECODE_SHAPES = [
     (2, 3, 1, 1000, 128), (1, 2, 1, 4097, 64), (1, 4, 1, 20000, 128), (1, 1, 1, 63, 64), (3, 2, 2, 777, 128),
+    (1, 1, 1, 1, 128), (2, 2, 1, 5, 64), (1, 3, 1, 257, 128),
 ]
 CHUNK_SHAPES = [
     (1, 2, 37, 1500, 128), (1, 2, 300, 2000, 64), (1, 1, 512, 512, 128), (2, 1, 100, 6000, 64),
 ]
 
 
+@pytest.fixture(params=["stream", "mfma"])
+def decode_kernel(request, monkeypatch):
+    """Both kernels a single-query problem can take: the register-streaming one and (FA_DECODE=mfma of
+    include/fa.h) the tile kernel every other shape runs."""
+    monkeypatch.setenv("FA_DECODE", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("nsplit", [0, 1, 3, 16, 1024])
 @pytest.mark.parametrize("shape", DECODE_SHAPES)
-def test_decode_shapes_elementwise(oracle, shape, nsplit, causal, dtype):
+def test_decode_shapes_elementwise(oracle, shape, nsplit, causal, dtype, decode_kernel):
     B, H, Nq, Nk, D = shape
-    print(f"case splitkv decode shape={shape} nsplit={nsplit} causal={causal} dtype={dtype}", flush=True)
+    print(f"case splitkv decode shape={shape} nsplit={nsplit} causal={causal} dtype={dtype} kernel={decode_kernel}", flush=True)
     rng = np.random.default_rng(hash((shape, causal, dtype)) % (2**32))
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
     scale = 1.0 / math.sqrt(D)
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
     o, lse, plan = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
     assert 1 <= plan.nsplit <= (Nk + 63) // 64
+    assert plan.streaming == int(Nq == 1 and decode_kernel == "stream")
     check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} nsplit={nsplit} causal={causal} dt={dtype}")
 
 
@@ -73,12 +83,14 @@ def test_rows_without_visible_keys(oracle):
     assert (I.bits_to_f64(o, I.BF16)[:, :, :100] == 0).all()
 
 
+@pytest.mark.parametrize("Nq", [1, 5])
 @pytest.mark.parametrize("scale", [-0.3, 0.0, 2.0])
-def test_unusual_scales_and_large_logits(oracle, scale):
-    """Large logits: the runs end with very different exponent references, which the merge must reconcile."""
-    print(f"case splitkv scale={scale}", flush=True)
+def test_unusual_scales_and_large_logits(oracle, scale, Nq):
+    """Large logits: the runs end with very different exponent references, which the merge must reconcile
+    (Nq = 1: in the streaming kernel, between the lane groups of a workgroup too)."""
+    print(f"case splitkv scale={scale} Nq={Nq}", flush=True)
     rng = np.random.default_rng(179)
-    q, k, v = (rand_bits(rng, (1, 2, n, 64), I.F16, m) for n, m in ((5, 2.0), (3000, 2.0), (3000, 1.0)))
+    q, k, v = (rand_bits(rng, (1, 2, n, 64), I.F16, m) for n, m in ((Nq, 2.0), (3000, 2.0), (3000, 1.0)))
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, I.F16)
     o, lse, _ = run_fa_fwd_splitkv(q, k, v, scale, True, I.F16, 9)
     check_against_oracle(o, lse, o_ref, lse_ref, I.F16, f"scale={scale}")
@@ -96,6 +108,27 @@ def test_one_dominant_key_in_one_run():
         kk[0, 0, pos] = I.f32_to_bits(I.bits_to_f64(q[0, 0, 0], I.F16).astype(np.float32) * 1000, I.F16)
         o, lse, _ = run_fa_fwd_splitkv(q, kk, v, 1.0, False, I.F16, 11)
         assert np.array_equal(o[0, 0, 0], v[0, 0, pos]), pos
+
+
+def test_streaming_and_tile_kernels_agree():
+    """The two kernels of the single-query case on the same inputs: both within the tolerance of the oracle
+    (checked above), and within fp32 rounding of each other apart from the tile kernel's 16-bit probabilities."""
+    print("case splitkv streaming vs tile kernel", flush=True)
+    import os
+    rng = np.random.default_rng(182)
+    for dtype, D in ((I.F16, 128), (I.BF16, 64)):
+        q, k, v = (rand_bits(rng, (2, 3, n, D), dtype) for n in (1, 9000, 9000))
+        res = {}
+        for kern in ("stream", "mfma"):
+            os.environ["FA_DECODE"] = kern
+            try:
+                res[kern] = run_fa_fwd_splitkv(q, k, v, 0.1, True, dtype, 0)
+            finally:
+                del os.environ["FA_DECODE"]
+        (o0, lse0, p0), (o1, lse1, p1) = res["stream"], res["mfma"]
+        assert p0.streaming == 1 and p1.streaming == 0
+        d = np.abs(I.bits_to_f64(o0, dtype) - I.bits_to_f64(o1, dtype))
+        assert d.max() <= (1e-3 if dtype == I.F16 else 8e-3) and np.abs(lse0 - lse1).max() <= 1e-5
 
 
 def test_matches_fa_fwd_and_ignores_workspace_contents(monkeypatch):
