@@ -273,3 +273,29 @@ def test_build_report_shows_register_only_kernels():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name
         assert rep["LDS Size [bytes/block]"] <= 160 * 1024, name
+
+
+def test_binding_structures_have_the_headers_sizes_and_offsets(tmp_path):
+    """A C program that includes include/fa.h prints sizeof and the offset of the last member of every structure
+    the ABI passes; the ctypes mirrors in the binding must agree (a member added on one side only would make the
+    library write past the end of the caller's structure)."""
+    import ctypes
+    import os
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "fa.h"\n'
+        'int main(void) {\n'
+        '  printf("%zu %zu\\n", sizeof(fa_plan_t), offsetof(fa_plan_t, tiles_total));\n'
+        '  printf("%zu %zu\\n", sizeof(fa_splitkv_plan_t), offsetof(fa_splitkv_plan_t, streaming));\n'
+        '  printf("%zu %zu\\n", sizeof(fa_mask_t), offsetof(fa_mask_t, kv_len));\n'
+        '  return 0;\n}\n')
+    exe = tmp_path / "sizes"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-I", inc, str(src), "-o", str(exe)], check=True)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    got = [tuple(int(x) for x in line.split()) for line in lines if line]
+    want = [(ctypes.sizeof(fa.FaPlan), fa.FaPlan.tiles_total.offset),
+            (ctypes.sizeof(fa.FaSplitKvPlan), fa.FaSplitKvPlan.streaming.offset),
+            (ctypes.sizeof(fa.FaMask), fa.FaMask.kv_len.offset)]
+    assert got == want

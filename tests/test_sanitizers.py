@@ -37,7 +37,7 @@ class Plan(ctypes.Structure):
                 ("tiles_visited", ctypes.c_longlong), ("tiles_total", ctypes.c_longlong)]
 class SPlan(ctypes.Structure):
     _fields_ = [("nsplit", ctypes.c_int), ("grid_x", ctypes.c_int), ("grid_y", ctypes.c_int), ("combine_grid", ctypes.c_int),
-                ("work_items", ctypes.c_longlong), ("workspace_bytes", ctypes.c_longlong)]
+                ("work_items", ctypes.c_longlong), ("workspace_bytes", ctypes.c_longlong), ("streaming", ctypes.c_int)]
 class Mask(ctypes.Structure):
     _fields_ = [("l", ctypes.c_int), ("r", ctypes.c_int), ("p", ctypes.c_int), ("kv", ctypes.c_void_p)]
 big = 2**31 - 1
