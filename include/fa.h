@@ -124,8 +124,9 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
  *   workspace_bytes : size of `workspace`
  *   everything else : as for fa_fwd
  *
- * Enqueues two kernels on `stream`, allocates nothing, does not synchronise.  Calls that share
- * a workspace must be ordered (same stream).  Returns FA_OK or a negative FA_ERR_* code; on an
+ * Enqueues two kernels on `stream` (one when a single-query problem needs a single run),
+ * allocates nothing, does not synchronise.  Calls that share a workspace must be ordered (same
+ * stream).  Returns FA_OK or a negative FA_ERR_* code; on an
  * argument error nothing is launched.
  */
 int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse,
@@ -135,7 +136,7 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
 typedef struct fa_splitkv_plan {
     int nsplit;                 /* runs actually used */
     int grid_x, grid_y;         /* first kernel: work items (tile kernel: rounded up to a multiple of 8) x runs */
-    int combine_grid;           /* second kernel: blocks of 256 threads */
+    int combine_grid;           /* second kernel: blocks of 256 threads (0: none, a single streaming run stores o itself) */
     long long work_items;       /* B * H * ceil(Nq / 256) */
     long long workspace_bytes;  /* nsplit * B * H * Nq * (D + 2) * 4 */
     int streaming;              /* 1: the register-streaming kernel of the single-query case, 0: the tile kernel */

@@ -1386,11 +1386,18 @@ __global__ __launch_bounds__(DECODE_WAVES * 64) void fa_decode_kernel(const FaPa
             L += sm_ml[q][1] * w;
             O += sm_o[q][tid] * w;
         }
-        const size_t row = (size_t)sp * gridDim.x + bh;
-        p.part_o[row * D + tid] = O;
-        if (tid == 0) {
-            const float2 ml = {M, L};
-            *(float2 *)(p.part_ml + row * 2) = ml;
+        if (p.nsplit == 1) {
+            // a single run is the whole result: normalise and store it here, no merge kernel follows
+            const float inv = L > 0.f ? 1.f / L : 0.f;
+            p.o[(size_t)bh * D + tid] = (uint16_t)pack2<DT>(O * inv, 0.f)[0];
+            if (tid == 0) p.lse[bh] = L > 0.f ? (M + __log2f(L)) * 0.6931471805599453f : -INFINITY;
+        } else {
+            const size_t row = (size_t)sp * gridDim.x + bh;
+            p.part_o[row * D + tid] = O;
+            if (tid == 0) {
+                const float2 ml = {M, L};
+                *(float2 *)(p.part_ml + row * 2) = ml;
+            }
         }
     }
 }
@@ -1452,7 +1459,7 @@ template <int DT, int D>
 hipError_t launch_decode(const FaParams &p, int heads, long long rows, hipStream_t stream) {
     hipLaunchKernelGGL((fa_decode_kernel<DT, D>), dim3(heads, p.nsplit), dim3(DECODE_WAVES * 64), 0, stream, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || p.nsplit == 1) return e;   // a single run stores o and lse itself
     constexpr int RPB = 256 / (D / 4);
     hipLaunchKernelGGL((fa_combine_kernel<DT, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream,
                        p.part_o, p.part_ml, p.o, p.lse, rows, p.nsplit);
@@ -1735,7 +1742,7 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
     plan->streaming = streaming ? 1 : 0;
     plan->grid_x = streaming ? (int)nwork : (int)(((nwork + 7) / 8) * 8);
     plan->grid_y = ns;
-    plan->combine_grid = (int)((rows + (1024 / D) - 1) / (1024 / D));
+    plan->combine_grid = streaming && ns == 1 ? 0 : (int)((rows + (1024 / D) - 1) / (1024 / D));
     plan->work_items = nwork;
     plan->workspace_bytes = (long long)ns * rows * (D + 2) * 4;
     return FA_OK;

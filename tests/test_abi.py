@@ -99,7 +99,8 @@ def test_splitkv_plan(lib, monkeypatch, decode_kernel):
     assert p.combine_grid == 3 and p.streaming == 0                               # 16 rows per block at D = 64
     # chosen: 256 workgroups, runs of at least four tiles, at least one run
     assert fa.fa_fwd_splitkv_plan(1, 32, 1, 32768, 128, 1, 1).nsplit == 8
-    assert fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 128, 1, 1).nsplit == 1
+    p = fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 128, 1, 1)
+    assert p.nsplit == 1 and p.combine_grid == (0 if stream else 32)   # a single streaming run needs no merge
     assert fa.fa_fwd_splitkv_plan(2, 24, 1, 32768, 128, 1, 1).nsplit == 6        # ceil(256 / 48)
     assert fa.fa_fwd_splitkv_plan(1, 8, 1, 2048, 128, 1, 1).nsplit == 8          # 32 tiles / 4
     # D = 64: 512 workgroups of the tile kernel (two fit a compute unit), 256 of the streaming kernel
