@@ -111,22 +111,23 @@ def time_decode(cfg, tensors, steps, warmup, torch, fa):
     return ev0.elapsed_time(ev1) / steps, plan
 
 
-def mfma_ceiling(torch, fa, dtype):
+def mfma_ceiling(torch, fa, dtype, operands):
     """TFLOP/s of a kernel that issues nothing but matrix instructions (fa_mfma_probe), sustained for about 0.3 s:
-    what the chip delivers under its power limit, to quote beside the nominal peak."""
+    what the chip delivers under its power limit, to quote beside the nominal peak.  operands = 0: the same
+    few-bit operands for every instruction; 1: pseudo-random operands that toggle from instruction to instruction."""
     scratch = torch.zeros(1, dtype=torch.float32, device="cuda:0")
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
     iters = 200000
     for _ in range(2):
-        flops = fa.fa_mfma_probe(dtype, iters, scratch, sp)
+        flops = fa.fa_mfma_probe(dtype, operands, iters, scratch, sp)
     torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     reps = 4
     ev0.record(stream)
     for _ in range(reps):
-        fa.fa_mfma_probe(dtype, iters, scratch, sp)
+        fa.fa_mfma_probe(dtype, operands, iters, scratch, sp)
     ev1.record(stream)
     torch.cuda.synchronize()
     return reps * flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
@@ -371,7 +372,8 @@ def main():
         tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
     wall_ms, event_ms, outputs = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
     spread = time_config.last_spread
-    ceiling = mfma_ceiling(torch, fa, cfg.dtype)
+    ceiling = mfma_ceiling(torch, fa, cfg.dtype, 0)
+    ceiling_random = mfma_ceiling(torch, fa, cfg.dtype, 1)
     flops = cfg.flops()
     plan = fa.fa_fwd_plan(cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, int(cfg.causal), cfg.dtype)
     value = flops / (wall_ms * 1e-3) / 1e12
@@ -384,6 +386,8 @@ def main():
         "dtype": "f16" if cfg.dtype == 0 else "bf16", "data": "synthetic",
         "pct_of_mfma_peak": round(100.0 * value / MFMA_PEAK_TFLOPS, 2),
         "mfma_only_ceiling_tflops": round(ceiling, 1), "pct_of_mfma_only_ceiling": round(100.0 * value / ceiling, 2),
+        "mfma_only_ceiling_random_operands_tflops": round(ceiling_random, 1),
+        "pct_of_mfma_only_ceiling_random_operands": round(100.0 * value / ceiling_random, 2),
         "launch_time_spread": spread,
         "config": {"workload": cfg.describe(), "flop_convention": "4*B*H*Nq*Nk*D, halved when causal",
                    "flops_exact_visible_pairs": 4.0 * cfg.D * cfg.visible_pairs(),

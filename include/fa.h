@@ -260,10 +260,13 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
  * v_mfma_f32_32x32x16 instructions of `dtype` (256 workgroups of 8 waves, `iters` x 4 instructions
  * per wave) and reports the floating-point operations it performs in *flops (HOST pointer).  Timed
  * by the caller, it gives the matrix throughput the chip sustains under its power limit -- the
- * practical ceiling to quote beside the nominal peak.  `scratch`: DEVICE pointer to one float
- * (never written in practice).  1 <= iters <= 2^24.
+ * practical ceiling to quote beside the nominal peak.  `operands`: 0 = one pair of operands with
+ * a few low bits set, the same for every instruction (hardly any switching: the friendliest case
+ * for the power limit); 1 = four pairs of pseudo-random operands taken in turn (signs and
+ * mantissas toggle from instruction to instruction, as with real data).  `scratch`: DEVICE
+ * pointer to one float (never written in practice).  1 <= iters <= 2^24.
  */
-int fa_mfma_probe(int dtype, int iters, float *scratch, long long *flops, void *stream);
+int fa_mfma_probe(int dtype, int operands, int iters, float *scratch, long long *flops, void *stream);
 
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);

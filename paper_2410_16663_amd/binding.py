@@ -102,7 +102,7 @@ def load() -> ctypes.CDLL:
         lib.fa_mask_interior_run.restype = ctypes.c_int
         lib.fa_mask_interior_run.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 7 + [ip, ip]
         lib.fa_mfma_probe.restype = ctypes.c_int
-        lib.fa_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_longlong), vp]
+        lib.fa_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_longlong), vp]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -250,10 +250,11 @@ def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_r
     return first.value, count.value
 
 
-def fa_mfma_probe(dtype, iters, scratch, stream=0) -> int:
+def fa_mfma_probe(dtype, operands, iters, scratch, stream=0) -> int:
     """fa_mfma_probe of include/fa.h: enqueue the matrix-only kernel, return the flop it performs."""
     flops = ctypes.c_longlong()
-    rc = load().fa_mfma_probe(int(dtype), int(iters), _addr(scratch), ctypes.byref(flops), _addr(stream))
+    rc = load().fa_mfma_probe(int(dtype), int(operands), int(iters), _addr(scratch), ctypes.byref(flops),
+                              _addr(stream))
     if rc != FA_OK:
         raise FaError(rc)
     return flops.value

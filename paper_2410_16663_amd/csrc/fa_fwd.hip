@@ -1191,20 +1191,33 @@ __global__ __launch_bounds__(512, 1) void fa_linear_kernel(const LinParams p) {
 // ---- ceiling probe: nothing but independent matrix instructions, two waves per SIMD on every compute unit.
 // What this reaches is what the chip sustains under its power limit with the matrix pipes saturated and nothing
 // else going on -- the practical ceiling beside the nominal peak.  Four accumulators per wave keep the pipe fed.
-template <int DT>
+// RANDOM = false: one pair of operands with a few low bits set, the same for every instruction (hardly any
+// switching in the multipliers: the friendliest case for the power limit).  RANDOM = true: four pairs of
+// operands with pseudo-random signs and mantissas, magnitudes in [0.5, 2) (fp16) or [2^-15, 2) (bf16),
+// taken in turn, so that consecutive instructions toggle the multiplier inputs the way real data does.
+template <int DT, bool RANDOM>
 __global__ __launch_bounds__(512, 1) void fa_mfma_probe_kernel(float *out, int iters) {
-    s16x8 a, b;
+    s16x8 a[4], b[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (short)(0x3c00 + ((threadIdx.x + i) & 7));   // small finite values in either format
-        b[i] = (short)(0x3800 + ((threadIdx.x + 3 * i) & 7));
-    }
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (RANDOM) {
+                unsigned x = (threadIdx.x * 8u + i) * 4u + n + 1u + blockIdx.x * 16384u;
+                x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;   // integer hash
+                a[n][i] = (short)(0x3800 | (x & 0x87ff));            // sign, 11 random low bits
+                b[n][i] = (short)(0x3800 | ((x >> 16) & 0x87ff));
+            } else {
+                a[n][i] = (short)(0x3c00 + ((threadIdx.x + i) & 7));   // small finite values in either format
+                b[n][i] = (short)(0x3800 + ((threadIdx.x + 3 * i) & 7));
+            }
+        }
     f32x16 c0 = (f32x16)(0.f), c1 = c0, c2 = c0, c3 = c0;
     for (int it = 0; it < iters; ++it) {
-        c0 = mfma32<DT>(a, b, c0);
-        c1 = mfma32<DT>(a, b, c1);
-        c2 = mfma32<DT>(a, b, c2);
-        c3 = mfma32<DT>(a, b, c3);
+        c0 = mfma32<DT>(a[0], b[0], c0);
+        c1 = mfma32<DT>(a[1], b[1], c1);
+        c2 = mfma32<DT>(a[2], b[2], c2);
+        c3 = mfma32<DT>(a[3], b[3], c3);
     }
     float s = 0.f;
 #pragma unroll
@@ -1212,11 +1225,6 @@ __global__ __launch_bounds__(512, 1) void fa_mfma_probe_kernel(float *out, int i
     if (s == 12345.678f) out[0] = s;                        // never true: keeps the loop alive
 }
 
-// Merge of the split-KV partial results (the same merge the split mode does between its two
-// wave groups): with M = max_s m_s, L = sum_s l_s 2^(m_s - M), the row is
-// o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
-// left m = -1e30, l = 0, acc = 0 and drops out; a row with no visible key at all gets o = 0,
-// lse = -inf.  One thread per (row, 4 consecutive d).
 // ---- decoding step (appendix C's decoding equations: one query row per head against the whole cache).
 // With a single query there is nothing for the matrix cores to reuse: every byte of K and V meets one
 // multiply-add, the bound is HBM, and the tile machinery of fa_fwd_kernel (LDS staging, barriers, 31 idle
@@ -1402,6 +1410,11 @@ __global__ __launch_bounds__(DECODE_WAVES * 64) void fa_decode_kernel(const FaPa
     }
 }
 
+// Merge of the split-KV partial results (the same merge the split mode does between its two
+// wave groups): with M = max_s m_s, L = sum_s l_s 2^(m_s - M), the row is
+// o = sum_s acc_s 2^(m_s - M) / L and lse = (M + log2 L) ln 2.  A run that saw no visible key
+// left m = -1e30, l = 0, acc = 0 and drops out; a row with no visible key at all gets o = 0,
+// lse = -inf.  One thread per (row, 4 consecutive d).
 template <int DT, int D>
 __global__ __launch_bounds__(256) void fa_combine_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                                          uint16_t *__restrict__ o, float *__restrict__ lse, long long rows,
@@ -1965,14 +1978,20 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
     return FA_OK;
 }
 
-int fa_mfma_probe(int dtype, int iters, float *scratch, long long *flops, void *stream) {
+int fa_mfma_probe(int dtype, int operands, int iters, float *scratch, long long *flops, void *stream) {
     if (!scratch || !flops) return FA_ERR_NULL;
     if (dtype != FA_DTYPE_F16 && dtype != FA_DTYPE_BF16) return FA_ERR_DTYPE;
+    if (operands != 0 && operands != 1) return FA_ERR_SHAPE;
     if (iters <= 0 || iters > (1 << 24)) return FA_ERR_SHAPE;
     if ((uintptr_t)scratch & 3) return FA_ERR_ALIGN;
     const int grid = 256;                                   // one workgroup of 8 waves per compute unit
-    if (dtype == FA_DTYPE_F16) hipLaunchKernelGGL((fa_mfma_probe_kernel<0>), dim3(grid), dim3(512), 0, (hipStream_t)stream, scratch, iters);
-    else hipLaunchKernelGGL((fa_mfma_probe_kernel<1>), dim3(grid), dim3(512), 0, (hipStream_t)stream, scratch, iters);
+    hipStream_t st = (hipStream_t)stream;
+    switch ((dtype << 1) | operands) {
+        case 0: hipLaunchKernelGGL((fa_mfma_probe_kernel<0, false>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
+        case 1: hipLaunchKernelGGL((fa_mfma_probe_kernel<0, true>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
+        case 2: hipLaunchKernelGGL((fa_mfma_probe_kernel<1, false>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
+        default: hipLaunchKernelGGL((fa_mfma_probe_kernel<1, true>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;

@@ -139,11 +139,12 @@ def test_probe_argument_errors(lib):
     import ctypes
     f = ctypes.c_longlong()
     L = fa.load()
-    assert L.fa_mfma_probe(0, 10, None, ctypes.byref(f), None) == fa.FA_ERR_NULL
-    assert L.fa_mfma_probe(0, 10, 0x1000, None, None) == fa.FA_ERR_NULL
-    assert L.fa_mfma_probe(2, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_DTYPE
-    assert L.fa_mfma_probe(0, 0, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
-    assert L.fa_mfma_probe(0, 10, 0x1002, ctypes.byref(f), None) == fa.FA_ERR_ALIGN
+    assert L.fa_mfma_probe(0, 0, 10, None, ctypes.byref(f), None) == fa.FA_ERR_NULL
+    assert L.fa_mfma_probe(0, 1, 10, 0x1000, None, None) == fa.FA_ERR_NULL
+    assert L.fa_mfma_probe(2, 0, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_DTYPE
+    assert L.fa_mfma_probe(0, 0, 0, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
+    assert L.fa_mfma_probe(0, 2, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
+    assert L.fa_mfma_probe(0, 1, 10, 0x1002, ctypes.byref(f), None) == fa.FA_ERR_ALIGN
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
@@ -268,8 +269,8 @@ def test_build_report_shows_register_only_kernels():
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
     # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
-    # heights; matrix-only probe: 2 dtypes; streaming decode: 2 dtypes x 2 head dims
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 2 + 4
+    # heights; matrix-only probe: 2 dtypes x 2 operand patterns; streaming decode: 2 dtypes x 2 head dims
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 4 + 4
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name
