@@ -12,6 +12,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "fa_fwd.hip")
 HDR = os.path.join(os.path.dirname(HERE), "include", "fa.h")
+# fragments of the one translation unit, included by fa_fwd.hip
+FRAGMENTS = [os.path.join(HERE, "csrc", n) for n in (
+    "fa_types.inc", "fa_mask.inc", "fa_device.inc", "fa_attention_kernel.inc", "fa_linear_kernel.inc",
+    "fa_probe_kernel.inc", "fa_decode_kernels.inc")]
 LIB = os.path.join(HERE, "libfa.so")
 
 HIPCC_FLAGS = [
@@ -31,7 +35,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in (SRC, HDR))
+    return any(os.path.getmtime(f) > t for f in [SRC, HDR] + FRAGMENTS)
 
 
 def parse_resource_report(stderr: str) -> dict:
