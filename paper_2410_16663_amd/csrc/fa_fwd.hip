@@ -278,6 +278,7 @@ FaParams base_params(const void *q, const void *k, const void *v, void *o, float
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.c = scale == 0.f ? 1.f : fabsf(scale) * LOG2E;
     p.nsplit = 1;
+    p.kv_stream = 0;
     p.part_o = nullptr;
     p.part_ml = nullptr;
     p.left = p.right = p.prefix = 0;
@@ -393,6 +394,7 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
 
     FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, ((long long)Nq + 255) / 256, pl.work_items, scale);
     p.nsplit = pl.nsplit;
+    p.kv_stream = Nq <= 256;
     p.part_o = (float *)workspace;
     p.part_ml = p.part_o + (size_t)pl.nsplit * rows * D;
     hipStream_t st = (hipStream_t)stream;
