@@ -18,6 +18,7 @@ int fa_oracle_attn_linear(const uint16_t *, const uint16_t *, const uint16_t *, 
 int fa_coop_plan_bytes(double, double, double, double, double, int, int, int *, int *);
 int fa_coop_plan_fp16(double, int, int, long long, long long, long long, long long, long long, long long, int *, int *);
 int fa_cpu_decode(const void *, const void *, const void *, void *, float *, int, int, int, int, float, int, int);
+int fa_cpu_stream_read(const void *, long long, int, int, double *, unsigned long long *);
 
 static uint32_t rng_state = 12345u;
 static uint16_t rand_half(void) {               /* a finite fp16 / bf16 pattern of moderate size */
@@ -59,6 +60,10 @@ int main(void) {
             CHECK(fa_cpu_decode(q1, k1, v1, o1, l1, B, H, 1, 64, 0.125f, dtype, 1));
             for (int i = 0; i < B * H; ++i)
                 if (!isfinite(l1[i])) { fprintf(stderr, "non-finite lse from fa_cpu_decode\n"); return 1; }
+            /* the streaming-read yardstick over a buffer that does not end on a 64-byte line */
+            double gbs;
+            unsigned long long chk;
+            CHECK(fa_cpu_stream_read(k1, (long long)sizeof(uint16_t) * B * H * 1000 * 64 - 6, 5, 2, &gbs, &chk));
             free(q); free(k); free(v); free(w); free(o); free(lse); free(p); free(y);
             free(q1); free(k1); free(v1); free(o1); free(l1);
         }
