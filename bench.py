@@ -405,7 +405,7 @@ def main():
                    "note": "Q,K,V,O of this workload (64 MiB) fit in the 256 MiB Infinity Cache"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic(cfg.name),
-                     "kernel": "fa_fwd_kernel (%s)" % {0: "split", 1: "wide", 2: "wide, folded rows"}[plan.mode],
+                     "kernel": "fa_fwd_kernel (%s)" % {0: "split", 1: "wide", 2: "wide, folded rows", 3: "streaming decode"}[plan.mode],
                      "avg_launch_ms": round(event_ms, 5),
                      "flops_per_launch": flops},
     }

@@ -79,13 +79,18 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * Nq > 768: WIDE_FOLD when Nq <= 4096, W <= 1024 and the last round of 256 workgroups is at
  * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); WIDE otherwise.
  * The environment variable FA_FWD_MODE=split|wide|fold overrides the choice (tests, tuning).
+ * Nq = 1 (one decoding step) takes none of these: FA_MODE_STREAM, the register-streaming kernel
+ * described at fa_fwd_splitkv, one workgroup per (batch, head) -- full speed when B*H fills the
+ * chip; with fewer heads fa_fwd_splitkv, which has a workspace to split the cache over, is the
+ * call to make.  FA_DECODE=mfma keeps Nq = 1 on the tile kernels.
  */
 #define FA_MODE_SPLIT 0
 #define FA_MODE_WIDE  1
 #define FA_MODE_WIDE_FOLD 2
+#define FA_MODE_STREAM 3   /* Nq = 1: the register-streaming kernel of fa_fwd_splitkv, one run per (batch, head) */
 
 typedef struct fa_plan {
-    int mode;                 /* FA_MODE_SPLIT, FA_MODE_WIDE or FA_MODE_WIDE_FOLD */
+    int mode;                 /* FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD or FA_MODE_STREAM */
     int block_m;              /* query rows per workgroup */
     int block_n;              /* keys per tile */
     int threads;              /* threads per workgroup */

@@ -31,6 +31,7 @@ FA_DTYPE_BF16 = 1
 FA_MODE_SPLIT = 0
 FA_MODE_WIDE = 1
 FA_MODE_WIDE_FOLD = 2
+FA_MODE_STREAM = 3
 
 # every symbol include/fa.h declares
 EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
@@ -67,6 +68,28 @@ class FaError(RuntimeError):
         super().__init__(f"fa error {code}: {fa_strerror(code)}")
 
 
+def _share_torchs_hip_runtime() -> None:
+    """One HIP runtime per process.  A PyTorch wheel ships its own libamdhip64.so and loads it by that file
+    name; libfa.so asks the loader for ``libamdhip64.so.7``.  When torch is imported first the loader hands
+    libfa.so torch's copy (same SONAME).  The other way round it would load the system's copy for libfa.so and,
+    later, torch's for torch: two runtimes with separate device state, and the first kernel launch through
+    libfa.so fails.  So if torch is installed but not imported yet, its copy is loaded here, globally, before
+    libfa.so: both then resolve to it (torch is located, not imported)."""
+    import importlib.util
+    import sys
+    if "torch" in sys.modules:
+        return
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        return
+    if spec is None or not spec.origin:
+        return
+    cand = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
 def load() -> ctypes.CDLL:
     """Load libfa.so (built by paper_2410_16663_amd.build); raises if it is not there."""
     global _lib
@@ -75,6 +98,7 @@ def load() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2410_16663_amd.build` "
                 "(there is no non-HIP fallback)")
+        _share_torchs_hip_runtime()
         lib = ctypes.CDLL(LIB_PATH)
         vp = ctypes.c_void_p
         lib.fa_fwd.restype = ctypes.c_int

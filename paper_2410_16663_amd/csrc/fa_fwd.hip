@@ -110,6 +110,13 @@ int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
     return FA_OK;
 }
 
+// One query row per head goes through the streaming kernel (FA_DECODE=mfma keeps the tile kernel: tests, tuning)
+bool use_streaming_decode(int Nq) {
+    if (Nq != 1) return false;
+    const char *env = getenv("FA_DECODE");
+    return !(env && !strcmp(env, "mfma"));
+}
+
 // Work decomposition for a problem, W = B * H * ceil(Nq / 256) being the number of 256-row workgroups
 // (the chip has 256 compute units and a D = 128 workgroup fills one).  From a sweep of forced modes
 // over 19 causal shapes:
@@ -187,13 +194,6 @@ int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in, bool
     if (n > SPLITKV_MAX) n = SPLITKV_MAX;
     if (n < 1) n = 1;
     return (int)n;
-}
-
-// One query row per head goes through the streaming kernel (FA_DECODE=mfma keeps the tile kernel: tests, tuning)
-bool use_streaming_decode(int Nq) {
-    if (Nq != 1) return false;
-    const char *env = getenv("FA_DECODE");
-    return !(env && !strcmp(env, "mfma"));
 }
 
 template <int DT, int D>
@@ -309,11 +309,23 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     if (!plan) return FA_ERR_NULL;
     const int rc = check_shape(B, H, Nq, Nk, D, dtype);
     if (rc != FA_OK) return rc;
+    const long long tiles_k = ((long long)Nk + BN - 1) / BN;
+    if (use_streaming_decode(Nq)) {
+        // one query per head (it sees every key, causal or not): fa_decode_kernel, one workgroup per (batch, head)
+        plan->mode = FA_MODE_STREAM;
+        plan->block_m = 1;
+        plan->block_n = BN;
+        plan->threads = DECODE_WAVES * 64;
+        plan->grid = B * H;
+        plan->work_items = (long long)B * H;
+        plan->tiles_visited = plan->tiles_total = (long long)B * H * tiles_k;
+        plan->lds_bytes = DECODE_WAVES * (512 / D) * (D + 2) * 4;     // one partial state per lane group
+        return FA_OK;
+    }
     const int mode = choose_mode(B, H, Nq, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
-    const long long tiles_k = ((long long)Nk + BN - 1) / BN;
     long long visited = 0;
     for (long long qt = 0; qt < nqt; ++qt) visited += tiles_walked(mode, nqt, qt, Nq, Nk, causal);
     plan->mode = mode;
@@ -337,7 +349,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
     if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
 
-    const int mode = choose_mode(B, H, Nq, causal);
+    const int mode = use_streaming_decode(Nq) ? FA_MODE_STREAM : choose_mode(B, H, Nq, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;   // query rows per workgroup
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
@@ -346,7 +358,18 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
 
-    const hipError_t e = launch_attention(p, mode, D, causal, dtype, grid, st);
+    hipError_t e;
+    if (mode == FA_MODE_STREAM) {
+        // a single query per head: the streaming kernel, one run per (batch, head), which stores o and lse itself
+        switch ((dtype << 1) | (D == 128)) {
+            case 0: e = launch_decode<0, 64>(p, (int)nwork, nwork, st); break;
+            case 1: e = launch_decode<0, 128>(p, (int)nwork, nwork, st); break;
+            case 2: e = launch_decode<1, 64>(p, (int)nwork, nwork, st); break;
+            default: e = launch_decode<1, 128>(p, (int)nwork, nwork, st); break;
+        }
+    } else {
+        e = launch_attention(p, mode, D, causal, dtype, grid, st);
+    }
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return FA_ERR_LAUNCH;

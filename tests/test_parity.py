@@ -7,6 +7,7 @@ import math
 import numpy as np
 import pytest
 
+from paper_2410_16663_amd import binding as fa
 from paper_2410_16663_amd import inputs as I
 from gpu_util import check_against_oracle, run_fa_fwd
 
@@ -184,3 +185,28 @@ def test_config_sampled_rows(oracle, monkeypatch, name):
     print(name, stats, flush=True)
     # cheap whole-tensor properties: everything written and finite
     assert np.isfinite(lse).all()
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 128), (2, 3, 77, 64), (3, 5, 1000, 128), (1, 2, 4097, 64), (16, 20, 300, 128)])
+def test_single_query_goes_through_the_streaming_kernel(oracle, monkeypatch, shape, dtype):
+    """fa_fwd with Nq = 1 (FA_MODE_STREAM): one run per (batch, head) of the streaming kernel, which stores o
+    and lse itself.  Causal or not is the same problem (the query sees every key); FA_DECODE=mfma sends it
+    through the tile kernels, whose result differs by the 16-bit rounding of the probabilities at most."""
+    B, H, Nk, D = shape
+    print(f"case fa_fwd single query shape={shape} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, dtype, 5)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (1, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    assert fa.fa_fwd_plan(B, H, 1, Nk, D, 1, dtype).mode == fa.FA_MODE_STREAM
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, dtype)
+    o_c, lse_c = run_fa_fwd(q, k, v, scale, True, dtype)
+    o_n, lse_n = run_fa_fwd(q, k, v, scale, False, dtype)
+    check_against_oracle(o_c, lse_c, o_ref, lse_ref, dtype, f"{shape} stream")
+    assert np.array_equal(o_c, o_n) and np.array_equal(lse_c, lse_n)
+    monkeypatch.setenv("FA_DECODE", "mfma")
+    assert fa.fa_fwd_plan(B, H, 1, Nk, D, 1, dtype).mode != fa.FA_MODE_STREAM
+    o_t, lse_t = run_fa_fwd(q, k, v, scale, True, dtype)
+    check_against_oracle(o_t, lse_t, o_ref, lse_ref, dtype, f"{shape} tile")
+    d = np.abs(I.bits_to_f64(o_c, dtype) - I.bits_to_f64(o_t, dtype))
+    assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2) and np.abs(lse_c - lse_t).max() <= 1e-5
