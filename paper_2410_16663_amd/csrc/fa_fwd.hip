@@ -184,9 +184,7 @@ constexpr long long DECODE_WORKGROUPS = 256;
 int choose_nsplit(long long nwork, long long tiles_k, int D, int nsplit_in, bool streaming) {
     long long n = nsplit_in;
     if (n <= 0) {
-        long long target = streaming ? DECODE_WORKGROUPS : (D == 128 ? 256 : 512);
-        if (streaming)
-            if (const char *env = getenv("FA_DECODE_WORKGROUPS")) { const long long v = atoll(env); if (v >= 1) target = v; }
+        const long long target = streaming ? DECODE_WORKGROUPS : (D == 128 ? 256 : 512);
         n = (target + nwork - 1) / nwork;
         if (n > tiles_k / 4) n = tiles_k / 4;
     }
