@@ -129,8 +129,9 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
  *   workspace_bytes : size of `workspace`
  *   everything else : as for fa_fwd
  *
- * Enqueues two kernels on `stream` (one when a single-query problem needs a single run),
- * allocates nothing, does not synchronise.  Calls that share a workspace must be ordered (same
+ * Enqueues two kernels on `stream` (with a single run, chosen or asked for, there is nothing
+ * to merge and the call enqueues exactly what fa_fwd would), allocates nothing, does not
+ * synchronise.  Calls that share a workspace must be ordered (same
  * stream).  Returns FA_OK or a negative FA_ERR_* code; on an
  * argument error nothing is launched.
  */
@@ -141,7 +142,7 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
 typedef struct fa_splitkv_plan {
     int nsplit;                 /* runs actually used */
     int grid_x, grid_y;         /* first kernel: work items (tile kernel: rounded up to a multiple of 8) x runs */
-    int combine_grid;           /* second kernel: blocks of 256 threads (0: none, a single streaming run stores o itself) */
+    int combine_grid;           /* second kernel: blocks of 256 threads (0: none -- with a single run the call is fa_fwd's launch) */
     long long work_items;       /* B * H * ceil(Nq / 256) */
     long long workspace_bytes;  /* nsplit * B * H * Nq * (D + 2) * 4 */
     int streaming;              /* 1: the register-streaming kernel of the single-query case, 0: the tile kernel */

@@ -392,7 +392,7 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
     plan->streaming = streaming ? 1 : 0;
     plan->grid_x = streaming ? (int)nwork : (int)(((nwork + 7) / 8) * 8);
     plan->grid_y = ns;
-    plan->combine_grid = streaming && ns == 1 ? 0 : (int)((rows + (1024 / D) - 1) / (1024 / D));
+    plan->combine_grid = ns == 1 ? 0 : (int)((rows + (1024 / D) - 1) / (1024 / D));   // a single run is fa_fwd's launch
     plan->work_items = nwork;
     plan->workspace_bytes = (long long)ns * rows * (D + 2) * 4;
     return FA_OK;
@@ -412,6 +412,9 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     if ((uintptr_t)workspace & 15) return FA_ERR_ALIGN;
     const long long rows = (long long)B * H * Nq;
     if (rows > 0x7fffffffLL * 8) return FA_ERR_SHAPE;   // combine grid
+    // a single run has nothing to merge: it is fa_fwd's launch (whose decompositions beat a one-run walk of
+    // the split-KV kernel by about 5% when there are enough query blocks to fill the chip without splitting)
+    if (pl.nsplit == 1) return fa_fwd(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream);
 
     FaParams p = base_params(q, k, v, o, lse, H, Nq, Nk, ((long long)Nq + 255) / 256, pl.work_items, scale);
     p.nsplit = pl.nsplit;

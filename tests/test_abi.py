@@ -96,11 +96,12 @@ def test_splitkv_plan(lib, monkeypatch, decode_kernel):
     assert (p.grid_x, p.grid_y, p.streaming) == ((3, 2, 1) if stream else (8, 2, 0))
     assert fa.fa_fwd_splitkv_plan(1, 1, 1, 130, 64, 0, 0, 50).nsplit == 3
     p = fa.fa_fwd_splitkv_plan(1, 1, 40, 130, 64, 0, 0, 1)
-    assert p.combine_grid == 3 and p.streaming == 0                               # 16 rows per block at D = 64
+    assert p.combine_grid == 0 and p.streaming == 0                               # one run: nothing to merge
+    assert fa.fa_fwd_splitkv_plan(1, 1, 40, 130, 64, 0, 0, 2).combine_grid == 3   # 16 rows per block at D = 64
     # chosen: 256 workgroups, runs of at least four tiles, at least one run
     assert fa.fa_fwd_splitkv_plan(1, 32, 1, 32768, 128, 1, 1).nsplit == 8
     p = fa.fa_fwd_splitkv_plan(8, 32, 1, 32768, 128, 1, 1)
-    assert p.nsplit == 1 and p.combine_grid == (0 if stream else 32)   # a single streaming run needs no merge
+    assert p.nsplit == 1 and p.combine_grid == 0                       # a single run needs no merge
     assert fa.fa_fwd_splitkv_plan(2, 24, 1, 32768, 128, 1, 1).nsplit == 6        # ceil(256 / 48)
     assert fa.fa_fwd_splitkv_plan(1, 8, 1, 2048, 128, 1, 1).nsplit == 8          # 32 tiles / 4
     # D = 64: 512 workgroups of the tile kernel (two fit a compute unit), 256 of the streaming kernel
