@@ -210,3 +210,32 @@ def test_single_query_goes_through_the_streaming_kernel(oracle, monkeypatch, sha
     check_against_oracle(o_t, lse_t, o_ref, lse_ref, dtype, f"{shape} tile")
     d = np.abs(I.bits_to_f64(o_c, dtype) - I.bits_to_f64(o_t, dtype))
     assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2) and np.abs(lse_c - lse_t).max() <= 1e-5
+
+
+def test_tensors_of_more_than_2_to_31_elements(oracle):
+    """B = 16, H = 32, N = 32768, D = 128: each tensor holds 2^31 elements (4 GiB), so every offset past the first
+    half of the tensors needs more than 32 bits.  The inputs are drawn on the GPU (2^33 bytes of normals would
+    take minutes on the host); three heads -- the first, one in the middle, the very last -- are copied back and
+    checked against the oracle on sampled rows, the last rows of the last head included."""
+    import torch
+    B, H, N, D, dtype = 16, 32, 32768, 128, I.BF16
+    print(f"case fa_fwd large tensors B={B} H={H} N={N} D={D}", flush=True)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    q, k, v = (torch.randn((B, H, N, D), generator=gen, device=dev, dtype=torch.bfloat16) for _ in range(3))
+    assert q.numel() == 2**31
+    o = torch.full((B, H, N, D), float("nan"), device=dev, dtype=torch.bfloat16)
+    lse = torch.full((B, H, N), float("nan"), device=dev, dtype=torch.float32)
+    scale = 1.0 / math.sqrt(D)
+    fa.fa_fwd(q, k, v, o, lse, B, H, N, N, D, scale, 1, dtype, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert not torch.isnan(lse).any().item()
+    rng = np.random.default_rng(4243)
+    for b, h in ((0, 0), (7, 13), (B - 1, H - 1)):
+        bits = [t[b, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(1, 1, N, D) for t in (q, k, v)]
+        rows = np.unique(np.concatenate([rng.integers(0, N, size=48), [0, 1, N - 2, N - 1]]))
+        o_ref, lse_ref = oracle.attention_fwd(bits[0], bits[1], bits[2], scale, True, dtype, rows=rows)
+        o_h = o[b, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)[rows]
+        lse_h = lse[b, h].cpu().numpy()[rows]
+        check_against_oracle(o_h, lse_h, o_ref, lse_ref, dtype, f"large tensors head {b},{h}")

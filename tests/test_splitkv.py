@@ -161,3 +161,35 @@ def test_decode_at_cache_size_on_sampled_heads(oracle):
         o_ref, lse_ref = oracle.attention_fwd(q[b:b + 1, h:h + 1], k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1],
                                               cfg.scale, cfg.causal, cfg.dtype)
         check_against_oracle(o[b:b + 1, h:h + 1], lse[b:b + 1, h:h + 1], o_ref, lse_ref, cfg.dtype, f"head {b},{h}")
+
+
+@pytest.mark.parametrize("kernel", ["stream", "mfma"])
+def test_cache_of_more_than_2_to_31_elements(oracle, monkeypatch, kernel):
+    """B = 64, H = 32, Nk = 8192, D = 128: K and V hold 2^31 elements each, so the last heads sit past 32-bit
+    offsets.  Inputs drawn on the GPU; the first, a middle and the very last head are checked against the oracle."""
+    import torch
+    from paper_2410_16663_amd import binding as fa
+    monkeypatch.setenv("FA_DECODE", kernel)
+    B, H, Nk, D, dtype = 64, 32, 8192, 128, I.F16
+    print(f"case splitkv large cache B={B} H={H} Nk={Nk} D={D} kernel={kernel}", flush=True)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4343)
+    q = torch.randn((B, H, 1, D), generator=gen, device=dev, dtype=torch.float16)
+    k, v = (torch.randn((B, H, Nk, D), generator=gen, device=dev, dtype=torch.float16) for _ in range(2))
+    assert k.numel() == 2**31
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((B, H, 1), float("nan"), device=dev, dtype=torch.float32)
+    scale = 1.0 / math.sqrt(D)
+    for nsplit in (0, 3):
+        plan = fa.fa_fwd_splitkv_plan(B, H, 1, Nk, D, 1, dtype, nsplit)
+        ws = torch.empty((plan.workspace_bytes + 3) // 4, device=dev, dtype=torch.float32)
+        fa.fa_fwd_splitkv(q, k, v, o, lse, B, H, 1, Nk, D, scale, 1, dtype, nsplit, ws, plan.workspace_bytes,
+                          torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert not torch.isnan(lse).any().item()
+        for b, h in ((0, 0), (31, 17), (B - 1, H - 1)):
+            qb, kb, vb = (t[b:b + 1, h:h + 1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16) for t in (q, k, v))
+            o_ref, lse_ref = oracle.attention_fwd(qb, kb, vb, scale, True, dtype)
+            o_h = o[b:b + 1, h:h + 1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            check_against_oracle(o_h, lse[b:b + 1, h:h + 1].cpu().numpy(), o_ref, lse_ref, dtype, f"head {b},{h} nsplit={nsplit}")
