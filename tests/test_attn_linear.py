@@ -134,3 +134,49 @@ def test_llama7b_layer_shape_on_sampled_tokens(oracle):
     check_y(y[0, rows], y_ref, "C2 projection sample")
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
     check_against_oracle(o, lse, o_ref, lse_ref, cfg.dtype, "C2 in blocks")
+
+
+def test_blocks_pipeline_with_a_consumer_on_a_second_stream():
+    """The use section 4.2 has in mind: after each block an event is recorded, and a second stream (default
+    priority) consumes that block's rows of y -- here it copies them, standing in for the exchange between devices
+    -- while the first stream goes on with the next block.  The copy must equal the result of running the blocks
+    one after another with no second stream, bit for bit."""
+    import torch
+    from paper_2410_16663_amd import binding as fa
+    print("case attn_linear two-stream pipeline", flush=True)
+    B, H, Nq, Nk, D, N, dtype = 2, 4, 1100, 1100, 128, 512, I.BF16
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(606)
+    q, k, v = (torch.randn((B, H, n, D), generator=gen, device=dev, dtype=torch.bfloat16) for n in (Nq, Nk, Nk))
+    w = (torch.randn((H * D, N), generator=gen, device=dev, dtype=torch.float32) / math.sqrt(H * D)).to(torch.bfloat16)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream(device=dev)
+    blocks = [(0, 128), (128, 256), (384, 256), (640, 256), (896, 204)]
+
+    def run(two_streams):
+        o = torch.zeros_like(q)
+        lse = torch.zeros((B, H, Nq), device=dev, dtype=torch.float32)
+        y = torch.full((B, Nq, N), float("nan"), device=dev, dtype=torch.float32)
+        y_out = torch.full_like(y, float("nan"))
+        torch.cuda.synchronize()
+        for r, n in blocks:
+            fa.fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, 0.09, 1, dtype, r, n, main.cuda_stream)
+            if two_streams:
+                ev = torch.cuda.Event()
+                ev.record(main)
+                side.wait_event(ev)
+                with torch.cuda.stream(side):
+                    y_out[:, r:r + n].copy_(y[:, r:r + n])
+            else:
+                y_out[:, r:r + n].copy_(y[:, r:r + n])
+        if two_streams:
+            main.wait_stream(side)
+        torch.cuda.synchronize()
+        return y_out.cpu().numpy(), y.cpu().numpy()
+
+    serial, y_serial = run(False)
+    assert np.isfinite(serial).all() and np.array_equal(serial, y_serial)
+    for _ in range(3):
+        piped, y_piped = run(True)
+        assert np.array_equal(piped, serial) and np.array_equal(y_piped, serial)
