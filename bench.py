@@ -198,7 +198,7 @@ def sliding_entry(I, torch, fa, steps, warmup):
                          "kernel": "fa_fwd_kernel (wide, descriptor mask)", "flops_per_launch": c.flops()}}
 
 
-def projection_entry(I, torch, fa, steps, warmup):
+def projection_entry(I, torch, fa, steps, warmup, overlap_demo=True):
     """Attention + output projection per block of rows (fa_attn_linear), priced against the MFMA peak:
     attention flop (causal convention) + 2 * tokens * (H*D) * N for the projection."""
     import math
@@ -283,14 +283,16 @@ def projection_entry(I, torch, fa, steps, warmup):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    t_compute = time_pipeline(overlap=False, comm=False)
-    t_comm = time_pipeline(overlap=False, compute=False)
-    t_serial = time_pipeline(overlap=False)
-    t_overlap = time_pipeline(overlap=True)
-    overlap_entry = {"stand_in": f"{COPIES} device copies of each block's rows of y on a second stream",
-                     "ms_compute_only": round(t_compute, 4), "ms_exchange_only": round(t_comm, 4),
-                     "ms_one_stream": round(t_serial, 4), "ms_two_streams": round(t_overlap, 4),
-                     "exchange_hidden_frac": round((t_serial - t_overlap) / t_comm, 3)}
+    overlap_entry = None
+    if overlap_demo:
+        t_compute = time_pipeline(overlap=False, comm=False)
+        t_comm = time_pipeline(overlap=False, compute=False)
+        t_serial = time_pipeline(overlap=False)
+        t_overlap = time_pipeline(overlap=True)
+        overlap_entry = {"stand_in": f"{COPIES} device copies of each block's rows of y on a second stream",
+                         "ms_compute_only": round(t_compute, 4), "ms_exchange_only": round(t_comm, 4),
+                         "ms_one_stream": round(t_serial, 4), "ms_two_streams": round(t_overlap, 4),
+                         "exchange_hidden_frac": round((t_serial - t_overlap) / t_comm, 3)}
     return {"workload": c.describe() + f" + projection {c.H * c.D}x{n_out}, blocks of {rpb} rows (first one half)",
             "overlap_with_exchange_stand_in": overlap_entry,
             "entry_point": "fa_attn_linear", "ms_per_call": round(ms, 4), "steps": steps,
@@ -383,6 +385,8 @@ def main():
                     help="time only the sliding-window workload through fa_fwd_masked (for profiling runs)")
     ap.add_argument("--projection-only", action="store_true",
                     help="time only the attention + output projection workload (for profiling runs)")
+    ap.add_argument("--overlap-demo", action="store_true",
+                    help="with --projection-only: also time the two-stream pipeline with the exchange stand-in")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
@@ -427,7 +431,8 @@ def main():
         print(json.dumps({"sliding": sliding_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
         return
     if args.projection_only:
-        print(json.dumps({"projection": projection_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
+        print(json.dumps({"projection": projection_entry(I, torch, fa, args.steps, args.warmup, args.overlap_demo)}),
+              flush=True)
         return
     if args.decode_only:
         print(json.dumps({"decode": decode_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
