@@ -115,3 +115,111 @@ def test_fa_attn_linear_random(oracle, monkeypatch, case):
     assert np.isfinite(y).all(), label
     err = np.abs(y.astype(np.float64) - y_ref)
     assert err.max() <= 1e-2 and err.mean() <= 1e-3, f"{label}: y max-abs {err.max():.3e} mean-abs {err.mean():.3e}"
+
+
+# ---- medium problems: several workgroups per head, several rounds of workgroups, long windows; the oracle is
+# asked for a seeded sample of rows only (first and last row always included)
+
+N_MEDIUM = 40
+
+
+def draw_medium(rng):
+    B = int(rng.integers(1, 3))
+    H = int(rng.integers(1, 9))
+    Nq = int(rng.integers(700, 6000))
+    Nk = Nq if rng.random() < 0.5 else int(rng.integers(700, 6000))
+    D = int(rng.choice([64, 128]))
+    dtype = int(rng.choice([I.F16, I.BF16]))
+    scale = float(rng.uniform(0.05, 0.12))
+    return B, H, Nq, Nk, D, dtype, scale
+
+
+def sample(rng, B, H, Nq, per_head=24):
+    """flat row ids (b*H + h)*Nq + i and the matching (b, h, i) index arrays"""
+    ids = []
+    for bh in range(B * H):
+        rows = np.unique(np.concatenate([rng.integers(0, Nq, size=per_head), [0, Nq - 1]]))
+        ids.append(bh * Nq + rows)
+    ids = np.concatenate(ids)
+    return ids, (ids // Nq) // H, (ids // Nq) % H, ids % Nq
+
+
+@pytest.mark.parametrize("case", range(N_MEDIUM))
+def test_fa_fwd_random_medium(oracle, monkeypatch, case):
+    rng = np.random.default_rng(11000 + case)
+    B, H, Nq, Nk, D, dtype, scale = draw_medium(rng)
+    causal = rng.random() < 0.7
+    mode = str(rng.choice(["auto", "split", "wide", "fold"]))
+    if mode != "auto":
+        monkeypatch.setenv("FA_FWD_MODE", mode)
+    label = f"fa_fwd medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} causal={causal} mode={mode}"
+    print("case " + label, flush=True)
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    ids, b, h, i = sample(rng, B, H, Nq)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype, rows=ids)
+    o, lse = run_fa_fwd(q, k, v, scale, causal, dtype)
+    check_against_oracle(o[b, h, i], lse[b, h, i], o_ref, lse_ref, dtype, label)
+
+
+@pytest.mark.parametrize("case", range(N_MEDIUM))
+def test_fa_fwd_masked_random_medium(oracle, case):
+    rng = np.random.default_rng(12000 + case)
+    B, H, Nq, Nk, D, dtype, scale = draw_medium(rng)
+
+    def limit():
+        r = rng.random()
+        return -1 if r < 0.25 else (0 if r < 0.4 else int(rng.integers(1, 4500)))
+    left, right = limit(), limit()
+    prefix = 0 if rng.random() < 0.5 else int(rng.integers(1, 3000))
+    kv_len = None if rng.random() < 0.6 else [int(rng.integers(Nk // 2, Nk + 1)) for _ in range(B)]
+    label = (f"masked medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} "
+             f"mask=({left},{right},{prefix},{kv_len})")
+    print("case " + label, flush=True)
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    ids, b, h, i = sample(rng, B, H, Nq)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, rows=ids)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+    check_against_oracle(o[b, h, i], lse[b, h, i], o_ref, lse_ref, dtype, label)
+
+
+@pytest.mark.parametrize("case", range(N_MEDIUM))
+def test_fa_fwd_splitkv_random_medium(oracle, monkeypatch, case):
+    rng = np.random.default_rng(13000 + case)
+    B, H, Nq, Nk, D, dtype, scale = draw_medium(rng)
+    Nq = int(rng.choice([1, 1, 2, 7, 64, 300, 1000]))
+    Nk = int(rng.integers(3000, 40000))
+    causal = bool(rng.integers(0, 2))
+    nsplit = int(rng.choice([0, 0, 2, 7, 31, 200]))
+    kern = str(rng.choice(["stream", "mfma"]))
+    monkeypatch.setenv("FA_DECODE", kern)
+    label = (f"splitkv medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} causal={causal} "
+             f"nsplit={nsplit} decode={kern}")
+    print("case " + label, flush=True)
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    ids, b, h, i = sample(rng, B, H, Nq, per_head=min(24, Nq))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype, rows=ids)
+    o, lse, _ = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
+    check_against_oracle(o[b, h, i], lse[b, h, i], o_ref, lse_ref, dtype, label)
+
+
+@pytest.mark.parametrize("case", range(N_MEDIUM // 2))
+def test_fa_attn_linear_random_medium(oracle, monkeypatch, case):
+    rng = np.random.default_rng(14000 + case)
+    B, H, Nq, Nk, D, dtype, scale = draw_medium(rng)
+    Nq = min(Nq, 3000)
+    Nk = max(Nk, Nq) if rng.random() < 0.5 else Nq
+    causal = bool(rng.integers(0, 2))
+    N = int(rng.choice([256, 1024]))
+    rpb = int(rng.choice([0, 256, 700, 1024]))
+    monkeypatch.setenv("FA_LINEAR_TILE", str(rng.choice(["128", "256"])))
+    label = (f"attn_linear medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} N={N} dt={dtype} causal={causal} "
+             f"rows_per_block={rpb}")
+    print("case " + label, flush=True)
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    w = rand_bits(rng, (H * D, N), dtype, 1.0 / math.sqrt(H * D))
+    tokens = np.unique(np.concatenate([rng.integers(0, B * Nq, size=40), [0, B * Nq - 1]]))
+    y_ref = oracle.attention_linear(q, k, v, w, scale, causal, dtype, rows=tokens)
+    o, lse, y = run_attn_linear(q, k, v, w, scale, causal, dtype, rows_per_block=rpb)
+    assert np.isfinite(y).all(), label
+    err = np.abs(y.reshape(B * Nq, N)[tokens].astype(np.float64) - y_ref)
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3, f"{label}: y max-abs {err.max():.3e} mean-abs {err.mean():.3e}"
