@@ -226,7 +226,10 @@ typedef struct fa_mask {
  * wave (32 query rows) and 64-key tile the kernel classifies the tile from the descriptor:
  * nothing visible -> not computed; everything visible -> no mask work; otherwise the predicate
  * is evaluated per element.  A workgroup (256 rows) only walks the prefix tiles and the tiles its
- * rows' windows touch.
+ * rows' windows touch.  Nq = 1 (a decoding step over caches of different lengths, or with a
+ * sliding window) runs the register-streaming kernel of fa_fwd_splitkv instead, one workgroup
+ * per (batch, head), which walks the prefix and the window as runs of consecutive keys
+ * (FA_DECODE=mfma keeps the tile kernel).
  */
 int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *lse,
                   int B, int H, int Nq, int Nk, int D, float scale, const fa_mask_t *mask, int dtype,

@@ -94,6 +94,13 @@ hipError_t launch_decode(const FaParams &p, int heads, long long rows, hipStream
     return hipGetLastError();
 }
 
+// single query under a mask descriptor: one workgroup per (batch, head), which stores o and lse itself
+template <int DT, int D>
+hipError_t launch_decode_masked(const FaParams &p, int heads, hipStream_t stream) {
+    hipLaunchKernelGGL((fa_decode_kernel<DT, D, true>), dim3(heads, 1), dim3(DECODE_WAVES * 64), 0, stream, p);
+    return hipGetLastError();
+}
+
 thread_local int g_last_hip_error = 0;
 
 
@@ -479,6 +486,20 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
+    if (use_streaming_decode(Nq)) {
+        // one query per head: the streaming kernel walks the prefix and the window as runs of consecutive keys
+        switch ((dtype << 1) | (D == 128)) {
+            case 0: e = launch_decode_masked<0, 64>(p, (int)nwork, st); break;
+            case 1: e = launch_decode_masked<0, 128>(p, (int)nwork, st); break;
+            case 2: e = launch_decode_masked<1, 64>(p, (int)nwork, st); break;
+            default: e = launch_decode_masked<1, 128>(p, (int)nwork, st); break;
+        }
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+        return FA_OK;
+    }
     switch ((dtype << 1) | (D == 128)) {
         case 0: e = launch_masked<0, 64>(p, grid, st); break;
         case 1: e = launch_masked<0, 128>(p, grid, st); break;

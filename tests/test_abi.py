@@ -270,8 +270,8 @@ def test_build_report_shows_register_only_kernels():
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
     # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
-    # heights; matrix-only probe: 2 dtypes x 2 operand patterns; streaming decode: 2 dtypes x 2 head dims
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 4 + 4
+    # heights; matrix-only probe: 2 dtypes x 2 operand patterns; streaming decode: 2 dtypes x 2 head dims x (plain, masked)
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 4 + 8
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

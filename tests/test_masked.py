@@ -108,3 +108,32 @@ def test_sliding_window_at_full_size_on_sampled_rows(oracle):
     rows = I.sample_rows(cfg, per_head=16)
     o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0, rows=rows)
     check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, "SWA sample")
+
+
+DECODE_MASKS = [
+    # left, right, prefix, per-batch key counts as fractions of Nk (None: no padding)
+    (-1, 0, 0, None), (-1, -1, 0, None), (0, 0, 0, None), (99, 0, 0, None), (4000, 0, 0, None), (-1, 0, 0, (1.0, 0.37, 0.0)),
+    (500, 0, 0, (0.9, 0.5, 1.0)), (300, 0, 64, None), (300, 0, 1000, None), (10, 0, 5000, None), (0, 0, 1, (0.5, 1.0, 0.001)),
+    (2000, 5, 128, (1.0, 0.999, 0.6)),
+]
+
+
+@pytest.mark.parametrize("kernel", ["stream", "mfma"])
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", DECODE_MASKS)
+def test_single_query_under_descriptor_masks(oracle, monkeypatch, mask, dtype, kernel):
+    """A decoding step (Nq = 1) over caches of different lengths, with a sliding window and / or a prefix that
+    stays visible: the streaming kernel walks the prefix and the window as two runs of consecutive keys (one if
+    they touch, none if the cache is empty); FA_DECODE=mfma keeps the tile kernel.  Both against the oracle."""
+    monkeypatch.setenv("FA_DECODE", kernel)
+    left, right, prefix, frac = mask
+    B, H, Nk = 3, 2, 3001
+    for D in (64, 128):
+        kv_len = None if frac is None else [int(round(f * Nk)) for f in frac]
+        print(f"case masked decode D={D} mask=({left},{right},{prefix},{kv_len}) dtype={dtype} kernel={kernel}", flush=True)
+        rng = np.random.default_rng(hash((mask[:3], dtype, D)) % (2**32))
+        q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (1, Nk, Nk))
+        scale = 1.0 / math.sqrt(D)
+        o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+        o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+        check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"masked decode D={D} {mask}")
