@@ -236,6 +236,26 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
                   void *stream);
 
 /*
+ * fa_decode_masked -- one decoding step (Nq = 1: q, o [B,H,1,D], lse [B,H]) under a descriptor mask, with the
+ * visible keys of every (batch, head) cut into `nsplit` equal shares as in fa_fwd_splitkv: the call for small
+ * batches of caches of different lengths (appendix C's decoding equations with section 4.1's generated mask),
+ * where B * H workgroups alone cannot fill the chip.  The query sits on the last key (diag = Nk - 1), so
+ * (-1, 0) lets it see kv_len[b] keys, (W - 1, 0) the last W of the Nk.  Each share is counted along the
+ * prefix and the window laid end to end, so entries with few keys are split as evenly as entries with many.
+ *
+ *   nsplit, workspace, workspace_bytes : as for fa_fwd_splitkv with Nq = 1; fa_fwd_splitkv_plan(B, H, 1, Nk, D,
+ *                     0, dtype, nsplit) reports the number of shares and the bytes (a single share needs no
+ *                     workspace: NULL is accepted then)
+ *   everything else : as for fa_fwd_masked
+ *
+ * Enqueues the streaming kernel and, with more than one share, the merge kernel on `stream`; allocates
+ * nothing; does not synchronise.  Same error codes as fa_fwd_masked and fa_fwd_splitkv.
+ */
+int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float *lse,
+                     int B, int H, int Nk, int D, float scale, const fa_mask_t *mask, int dtype,
+                     int nsplit, void *workspace, long long workspace_bytes, void *stream);
+
+/*
  * The tile classification and the workgroup's walk, callable on the host (the kernel runs the
  * same code): for tests and for callers that want to know the work a mask leaves.
  * kv_len here is ONE batch entry's key count (host int, 0..Nk); mask->kv_len is not read.

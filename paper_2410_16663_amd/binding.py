@@ -36,7 +36,8 @@ FA_MODE_STREAM = 3
 # every symbol include/fa.h declares
 EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
            "fa_attn_linear", "fa_mask_tile_class",
-           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_mfma_probe", "fa_strerror", "fa_version", "fa_last_hip_error")
+           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_mfma_probe", "fa_strerror", "fa_version", "fa_last_hip_error",
+           "fa_decode_masked")
 
 _lib = None
 
@@ -119,6 +120,9 @@ def load() -> ctypes.CDLL:
         lib.fa_fwd_masked.restype = ctypes.c_int
         lib.fa_fwd_masked.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
             ctypes.c_float, ctypes.POINTER(FaMask), ctypes.c_int, vp]
+        lib.fa_decode_masked.restype = ctypes.c_int
+        lib.fa_decode_masked.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 4 + [
+            ctypes.c_float, ctypes.POINTER(FaMask), ctypes.c_int, ctypes.c_int, vp, ctypes.c_longlong, vp]
         lib.fa_mask_tile_class.restype = ctypes.c_int
         lib.fa_mask_tile_class.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 6
         lib.fa_mask_tile_walk.restype = ctypes.c_int
@@ -236,6 +240,24 @@ def fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, pref
 def fa_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0) -> None:
     """fa_fwd_masked of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
     rc = fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_decode_masked_raw(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit, workspace,
+                         workspace_bytes, stream=0) -> int:
+    """Call fa_decode_masked (mask fields passed one by one) and return its status code unchanged."""
+    m = _mask(left, right, prefix, kv_len)
+    return load().fa_decode_masked(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nk), int(D),
+                                   float(scale), ctypes.byref(m), int(dtype), int(nsplit), _addr(workspace),
+                                   int(workspace_bytes), _addr(stream))
+
+
+def fa_decode_masked(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit, workspace,
+                     workspace_bytes, stream=0) -> None:
+    """fa_decode_masked of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_decode_masked_raw(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit,
+                              workspace, workspace_bytes, stream)
     if rc != FA_OK:
         raise FaError(rc)
 

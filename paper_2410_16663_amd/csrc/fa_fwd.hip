@@ -94,10 +94,15 @@ hipError_t launch_decode(const FaParams &p, int heads, long long rows, hipStream
     return hipGetLastError();
 }
 
-// single query under a mask descriptor: one workgroup per (batch, head), which stores o and lse itself
+// single query under a mask descriptor: p.nsplit workgroups per (batch, head); a single one stores o and lse itself
 template <int DT, int D>
 hipError_t launch_decode_masked(const FaParams &p, int heads, hipStream_t stream) {
-    hipLaunchKernelGGL((fa_decode_kernel<DT, D, true>), dim3(heads, 1), dim3(DECODE_WAVES * 64), 0, stream, p);
+    hipLaunchKernelGGL((fa_decode_kernel<DT, D, true>), dim3(heads, p.nsplit), dim3(DECODE_WAVES * 64), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.nsplit == 1) return e;
+    constexpr int RPB = 256 / (D / 4);
+    hipLaunchKernelGGL((fa_combine_kernel<DT, D>), dim3((unsigned)((heads + RPB - 1) / RPB)), dim3(256), 0, stream,
+                       p.part_o, p.part_ml, p.o, p.lse, (long long)heads, p.nsplit);
     return hipGetLastError();
 }
 
@@ -506,6 +511,47 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
         case 2: e = launch_masked<1, 64>(p, grid, st); break;
         case 3: e = launch_masked<1, 128>(p, grid, st); break;
         default: return FA_ERR_SHAPE;
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return FA_ERR_LAUNCH;
+    }
+    return FA_OK;
+}
+
+int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nk, int D,
+                     float scale, const fa_mask_t *mask, int dtype, int nsplit, void *workspace,
+                     long long workspace_bytes, void *stream) {
+    if (!q || !k || !v || !o || !lse || !mask) return FA_ERR_NULL;
+    fa_splitkv_plan_t pl;
+    const int rc = fa_fwd_splitkv_plan(B, H, 1, Nk, D, 0, dtype, nsplit, &pl);
+    if (rc != FA_OK) return rc;
+    if (!isfinite(scale)) return FA_ERR_SCALE;
+    MaskGeom g;
+    const int mrc = mask_geometry(mask, Nk, 1, Nk, &g);
+    if (mrc != FA_OK) return mrc;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
+    if (((uintptr_t)lse | (uintptr_t)mask->kv_len) & 3) return FA_ERR_ALIGN;
+    if (pl.nsplit > 1) {
+        if (!workspace || workspace_bytes < pl.workspace_bytes) return FA_ERR_WORKSPACE;
+        if ((uintptr_t)workspace & 15) return FA_ERR_ALIGN;
+    }
+    const long long heads = (long long)B * H;
+    FaParams p = base_params(q, k, v, o, lse, H, 1, Nk, 1, heads, scale);
+    p.left = g.left;
+    p.right = g.right;
+    p.prefix = mask->prefix < Nk ? mask->prefix : Nk;
+    p.kv_len = mask->kv_len;
+    p.nsplit = pl.nsplit;
+    p.part_o = (float *)workspace;
+    p.part_ml = p.part_o + (size_t)pl.nsplit * heads * D;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    switch ((dtype << 1) | (D == 128)) {
+        case 0: e = launch_decode_masked<0, 64>(p, (int)heads, st); break;
+        case 1: e = launch_decode_masked<0, 128>(p, (int)heads, st); break;
+        case 2: e = launch_decode_masked<1, 64>(p, (int)heads, st); break;
+        default: e = launch_decode_masked<1, 128>(p, (int)heads, st); break;
     }
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;

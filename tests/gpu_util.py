@@ -72,6 +72,30 @@ def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, p
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy()
 
 
+def run_fa_decode_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None, nsplit=0):
+    """One decoding step through fa_decode_masked (q_bits [B,H,1,D]); the workspace is filled with NaN first.
+    Returns (o_bits, lse, plan)."""
+    import torch
+    assert torch.cuda.is_available()
+    B, H, Nq, D = q_bits.shape
+    assert Nq == 1
+    Nk = k_bits.shape[2]
+    dev = torch.device("cuda:0")
+    tq = torch.from_numpy(q_bits.view(np.int16)).to(dev)
+    tk = torch.from_numpy(k_bits.view(np.int16)).to(dev)
+    tv = torch.from_numpy(v_bits.view(np.int16)).to(dev)
+    to = torch.full((B, H, 1, D), 0x7E00 if dtype == I.F16 else 0x7FC0, dtype=torch.int16, device=dev)
+    tl = torch.full((B, H, 1), float("nan"), dtype=torch.float32, device=dev)
+    tlen = None if kv_len is None else torch.tensor(list(kv_len), dtype=torch.int32, device=dev)
+    plan = fa.fa_fwd_splitkv_plan(B, H, 1, Nk, D, 0, dtype, nsplit)
+    ws = torch.full(((plan.workspace_bytes + 3) // 4 + 4,), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    fa.fa_decode_masked(tq, tk, tv, to, tl, B, H, Nk, D, scale, left, right, prefix, tlen, dtype, nsplit, ws,
+                        plan.workspace_bytes, stream)
+    torch.cuda.synchronize()
+    return to.cpu().numpy().view(np.uint16), tl.cpu().numpy(), plan
+
+
 def run_attn_linear(q_bits, k_bits, v_bits, w_bits, scale, causal, dtype, blocks=None, rows_per_block=0):
     """fa_attn_linear (blocks=None) or one fa_attn_linear_block call per (row_first, row_count) in ``blocks``.
     Outputs are poisoned first.  Returns (o_bits, lse, y) as numpy."""

@@ -179,6 +179,26 @@ def test_masked_argument_errors_come_back_before_any_launch(lib, change, code):
     assert e.value.code == code
 
 
+DEC_GOOD = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=2, H=4, Nk=6400, D=128, scale=0.1,
+                left=-1, right=0, prefix=0, kv_len=0x7000, dtype=1, nsplit=4, workspace=0x8000, workspace_bytes=1 << 30)
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(k=0), fa.FA_ERR_NULL), (dict(Nk=0), fa.FA_ERR_SHAPE), (dict(D=96), fa.FA_ERR_HEADDIM),
+    (dict(dtype=2), fa.FA_ERR_DTYPE), (dict(scale=float("nan")), fa.FA_ERR_SCALE), (dict(prefix=-3), fa.FA_ERR_MASK),
+    (dict(kv_len=0x7001), fa.FA_ERR_ALIGN), (dict(nsplit=5000), fa.FA_ERR_NSPLIT),
+    (dict(workspace=0), fa.FA_ERR_WORKSPACE), (dict(workspace_bytes=4 * 2 * 4 * 130 * 4 - 1), fa.FA_ERR_WORKSPACE),
+    (dict(workspace=0x8004), fa.FA_ERR_ALIGN), (dict(Nk=2**30), fa.FA_ERR_SHAPE),
+])
+def test_decode_masked_argument_errors_come_back_before_any_launch(lib, change, code):
+    args = dict(DEC_GOOD)
+    args.update(change)
+    assert fa.fa_decode_masked_raw(**args) == code
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_decode_masked(**args)
+    assert e.value.code == code
+
+
 def test_null_descriptor_and_bad_host_queries(lib):
     L = fa.load()
     assert L.fa_fwd_masked(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 8, 8, 64, 0.1, None, 0, None) == fa.FA_ERR_NULL

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from paper_2410_16663_amd import inputs as I
-from gpu_util import check_against_oracle, run_fa_fwd, run_fa_fwd_masked
+from gpu_util import check_against_oracle, run_fa_decode_masked, run_fa_fwd, run_fa_fwd_masked
 
 pytestmark = pytest.mark.gpu
 
@@ -137,3 +137,23 @@ def test_single_query_under_descriptor_masks(oracle, monkeypatch, mask, dtype, k
         o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
         o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
         check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"masked decode D={D} {mask}")
+
+
+@pytest.mark.parametrize("nsplit", [0, 1, 2, 7, 40])
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", DECODE_MASKS)
+def test_decode_masked_in_shares(oracle, mask, dtype, nsplit):
+    """fa_decode_masked: the same step with every (batch, head)'s visible keys -- prefix and window laid end to
+    end -- cut into nsplit shares and merged.  Entries with few or no keys get shares of few or no keys."""
+    left, right, prefix, frac = mask
+    B, H, Nk = 3, 2, 3001
+    for D in (64, 128):
+        kv_len = None if frac is None else [int(round(f * Nk)) for f in frac]
+        print(f"case decode masked shares D={D} mask=({left},{right},{prefix},{kv_len}) dtype={dtype} nsplit={nsplit}", flush=True)
+        rng = np.random.default_rng(hash((mask[:3], dtype, D, 9)) % (2**32))
+        q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (1, Nk, Nk))
+        scale = 1.0 / math.sqrt(D)
+        o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+        o, lse, plan = run_fa_decode_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, nsplit)
+        assert plan.nsplit >= 1 and (nsplit == 0 or plan.nsplit == min(nsplit, (Nk + 63) // 64))
+        check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"decode masked shares D={D} {mask} nsplit={nsplit}")
