@@ -27,6 +27,7 @@ def test_entry_points_replay_from_a_graph():
     scale = 1.0 / math.sqrt(D)
     plan = fa.fa_fwd_splitkv_plan(B, H, 1, Nk, D, 1, dtype, 5)
     ws = torch.empty((plan.workspace_bytes + 3) // 4, dtype=torch.float32, device=dev)
+    ws2 = torch.empty_like(ws)
     klen = torch.tensor([700, 333], dtype=torch.int32, device=dev)
 
     def outputs():
@@ -38,6 +39,8 @@ def test_entry_points_replay_from_a_graph():
                     lsem=torch.zeros((B, H, Nq), dtype=torch.float32, device=dev),
                     ol=torch.zeros((B, H, Nq, D), dtype=torch.int16, device=dev),
                     lsel=torch.zeros((B, H, Nq), dtype=torch.float32, device=dev),
+                    od=torch.zeros((B, H, 1, D), dtype=torch.int16, device=dev),
+                    lsed=torch.zeros((B, H, 1), dtype=torch.float32, device=dev),
                     y=torch.zeros((B, Nq, N), dtype=torch.float32, device=dev))
 
     def enqueue(t, stream):
@@ -46,6 +49,8 @@ def test_entry_points_replay_from_a_graph():
                           stream)
         fa.fa_fwd_masked(q, k, v, t["om"], t["lsem"], B, H, Nq, Nk, D, scale, 200, 0, 64, klen, dtype, stream)
         fa.fa_attn_linear(q, k, v, w, t["ol"], t["lsel"], t["y"], B, H, Nq, Nk, D, N, scale, 1, dtype, 256, stream)
+        fa.fa_decode_masked(q1, k, v, t["od"], t["lsed"], B, H, Nk, D, scale, 300, 0, 32, klen, dtype, 5, ws2,
+                            plan.workspace_bytes, stream)
 
     eager = outputs()
     enqueue(eager, torch.cuda.current_stream().cuda_stream)        # also loads the kernels before any capture
@@ -62,6 +67,7 @@ def test_entry_points_replay_from_a_graph():
         for t in captured.values():
             t.zero_()                                              # eager work between replays
         ws.fill_(float("nan"))
+        ws2.fill_(float("nan"))
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
