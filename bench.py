@@ -2,9 +2,13 @@
 """Benchmark of the attention forward on one MI355X.
 
 A step is one fa_fwd launch over one batch of synthetic input already resident in HBM.
-Prints ONE JSON line: whole-job TFLOP/s on the headline workload (benchmark configs[1]),
-the roofline figures of the kernel measured with HIP events on the launch stream, the CPU
-oracle timed on the host cores, and (unless --no-extra) the other full-size configurations.
+Prints ONE JSON line: whole-job TFLOP/s on the headline workload -- C5, the long-context causal
+configuration (B=1, H=32, N=131072, D=128, bf16), the largest of the benchmark's configurations and the
+one the ">= 50% of MFMA peak on the causal long-sequence configurations" target is about -- with the
+roofline figures of the kernel measured with HIP events on the launch stream, the output of the timed
+launches checked against the CPU oracle (every element for C1/C2, the seeded sample of 64 rows per head
+for C3-C5), the oracle timed on the host cores, and (unless --no-extra) the other configurations, each
+with its own roofline entry.
 
 FLOP convention (section 5.2.3 of the paper, times the batch): 4*B*H*Nq*Nk*D, halved when causal.
 """
@@ -46,8 +50,13 @@ def device_inputs_on_gpu(cfg, torch):
     return tuple(out)
 
 
+MIN_WARM_S = 0.5   # the untimed warm-up lasts at least this long, so that the timed steps run at sustained clocks
+
+
 def time_config(cfg, tensors, steps, warmup, torch, fa):
-    """Warm up, then time exactly `steps` launches. Returns wall ms/step and the HIP-event mean ms/launch."""
+    """Warm up (`warmup` launches, and on until MIN_WARM_S seconds have passed: the warm-up is untimed, and a
+    timed region that starts on a GPU still ramping its clocks reads 10% low), then time exactly `steps`
+    launches.  Returns wall ms/step and the HIP-event mean ms/launch."""
     tq, tk, tv = tensors
     dev = tq.device
     to = torch.empty((cfg.B, cfg.H, cfg.Nq, cfg.D), dtype=torch.int16, device=dev)
@@ -58,9 +67,14 @@ def time_config(cfg, tensors, steps, warmup, torch, fa):
     def launch():
         fa.fa_fwd(tq, tk, tv, to, tl, cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, cfg.scale, int(cfg.causal), cfg.dtype, sp)
 
-    for _ in range(warmup):
-        launch()
-    torch.cuda.synchronize()
+    t_w = time.perf_counter()
+    done = 0
+    while done < warmup or time.perf_counter() - t_w < MIN_WARM_S:
+        for _ in range(max(1, min(warmup, 50))):
+            launch()
+        done += max(1, min(warmup, 50))
+        torch.cuda.synchronize()
+    time_config.last_warmup_launches = done
     # HIP events on the stream the kernel is launched on: one pair around all the steps, and one event per chunk
     # of steps (at most 20 chunks) for the spread
     nchunk = min(20, steps)
@@ -111,8 +125,8 @@ def time_decode(cfg, tensors, steps, warmup, torch, fa):
     return ev0.elapsed_time(ev1) / steps, plan
 
 
-def mfma_ceiling(torch, fa, dtype, operands):
-    """TFLOP/s of a kernel that issues nothing but matrix instructions (fa_mfma_probe), sustained for about 0.3 s:
+def mfma_ceiling(torch, fb, dtype, operands):
+    """TFLOP/s of a kernel that issues nothing but matrix instructions (fa_mfma_probe of include/fa_bench.h), sustained for about 0.3 s:
     what the chip delivers under its power limit, to quote beside the nominal peak.  operands = 0: the same
     few-bit operands for every instruction; 1: pseudo-random operands that toggle from instruction to instruction."""
     scratch = torch.zeros(1, dtype=torch.float32, device="cuda:0")
@@ -120,30 +134,36 @@ def mfma_ceiling(torch, fa, dtype, operands):
     sp = stream.cuda_stream
     iters = 200000
     for _ in range(2):
-        flops = fa.fa_mfma_probe(dtype, operands, iters, scratch, sp)
+        flops = fb.fa_mfma_probe(dtype, operands, iters, scratch, sp)
     torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     reps = 4
     ev0.record(stream)
     for _ in range(reps):
-        fa.fa_mfma_probe(dtype, operands, iters, scratch, sp)
+        fb.fa_mfma_probe(dtype, operands, iters, scratch, sp)
     ev1.record(stream)
     torch.cuda.synchronize()
     return reps * flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
 
 
 def read_traffic(workload, stem="fa_fwd"):
-    """HBM bytes per launch (per call for the entry points that enqueue several kernels) from the committed
-    rocprofv3 --pmc summary, or None."""
-    path = os.path.join(ROOT, "profiles", f"{stem}_{workload}_hbm_traffic.txt")
+    """HBM bytes per launch (per call for the entry points that enqueue several kernels).  NOT measured in this
+    run: read from the committed summary of a separate rocprofv3 --pmc run (counters cannot be collected from
+    inside the benchmark).  Returns (bytes or None, the file it came from or None)."""
+    rel = os.path.join("profiles", f"{stem}_{workload}_hbm_traffic.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:") or line.startswith("traffic_bytes_per_call:"):
-                return float(line.split(":", 1)[1])
+                return float(line.split(":", 1)[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def traffic_fields(workload, stem="fa_fwd"):
+    t, src = read_traffic(workload, stem)
+    return {"traffic": t, "traffic_source": (src + " (separate rocprofv3 --pmc run, not this run)") if src else None}
 
 
 def decode_entry(I, torch, fa, steps, warmup):
@@ -158,7 +178,7 @@ def decode_entry(I, torch, fa, steps, warmup):
             "grid": [plan.grid_x, plan.grid_y], "ms_per_call": round(ms, 5), "steps": steps,
             "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic("splitkv_DEC"),
+                         "frac": round(gbs / HBM_PEAK_GBS, 4), **traffic_fields("splitkv_DEC"),
                          "kernel": ("fa_decode_kernel" if plan.streaming else "fa_fwd_kernel (wide, split-KV)")
                                    + " + fa_combine_kernel",
                          "bytes_per_call": kv_bytes}}
@@ -194,7 +214,7 @@ def sliding_entry(I, torch, fa, steps, warmup):
             "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
             "flop_convention": "4*D per attending (query, key) pair, counted exactly",
             "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic("masked_SWA"),
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("masked_SWA"),
                          "kernel": "fa_fwd_kernel (wide, descriptor mask)", "flops_per_launch": c.flops()}}
 
 
@@ -298,7 +318,7 @@ def projection_entry(I, torch, fa, steps, warmup, overlap_demo=True):
             "entry_point": "fa_attn_linear", "ms_per_call": round(ms, 4), "steps": steps,
             "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds); w ~ N(0,1)/sqrt(H*D)",
             "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic("LIN", "fa_attn_linear"),
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("LIN", "fa_attn_linear"),
                          "kernel": "fa_fwd_kernel + fa_linear_kernel, per block",
                          "flops_per_call": fl_attn + fl_proj, "flops_attention": fl_attn, "flops_projection": fl_proj}}
 
@@ -343,6 +363,7 @@ def cpu_decode_entry(I, np):
     """The host-side decoding attention of the cooperative strategy (fa_cpu_decode) on one GPU's share of the
     decoding workload's heads, timed on the machine's host cores; bytes = K and V read once."""
     from paper_2410_16663_amd import cpu_binding as fc
+    from paper_2410_16663_amd import bench_binding as fb
     c = I.DECODE
     B, H = 1, 32    # 512 MiB of K and V: far beyond the host's caches
     q = I.normal_bits((B, H, 1, c.D), c.seeds[0], c.dtype)
@@ -361,26 +382,102 @@ def cpu_decode_entry(I, np):
     kv_bytes = 2.0 * B * H * c.Nk * c.D * 2
     gbs = kv_bytes / (ms * 1e-3) / 1e9
     # the yardstick: the same threads adding up the same K and V buffers, nothing else
-    fc.fa_cpu_stream_read(k, k.nbytes, 0, 1)
-    stream = 0.5 * (fc.fa_cpu_stream_read(k, k.nbytes, 0, 5)[0] + fc.fa_cpu_stream_read(v, v.nbytes, 0, 5)[0])
+    fb.fa_cpu_stream_read(k, k.nbytes, 0, 1)
+    stream = 0.5 * (fb.fa_cpu_stream_read(k, k.nbytes, 0, 5)[0] + fb.fa_cpu_stream_read(v, v.nbytes, 0, 5)[0])
     return {"workload": f"B={B} H={H} Nq=1 Nk={c.Nk} D={c.D} bf16 (host memory)", "entry_point": "fa_cpu_decode",
             "ms_per_call": round(ms, 4), "gb_per_s": round(gbs, 2),
             "threads": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "avx512": fc.fa_cpu_has_avx512(),
             "bytes_per_call": kv_bytes,
             "roofline": {"bound": "host memory", "achieved": round(gbs, 1), "peak": round(stream, 1), "unit": "GB/s",
                          "frac": round(gbs / stream, 4), "traffic": None,
-                         "peak_is": "fa_cpu_stream_read over the same buffers on the same threads (measured, "
+                         "peak_is": "fa_cpu_stream_read (include/fa_bench.h) over the same buffers on the same threads (measured, "
                                     "not a published figure)"}}
+
+
+FULL_ORACLE = ("C1", "C2")    # checked element by element; the others on the seeded sample of 64 rows per (b, h)
+
+
+def oracle_leg(cfg, host, outputs, np, I, time_it):
+    """The timed launches' output against the fp64 oracle -- every element for C1/C2, the seeded stratified sample
+    of 64 rows per (batch, head) (inputs.sample_rows) for C3-C5, whose full oracle would take hours -- and, with
+    time_it, the oracle itself timed on the host cores over the same rows (whole passes until about 20
+    core-seconds are spent).  Returns (parity dict, cpu_baseline dict or None)."""
+    import oracle
+    q, k, v = host
+    nthreads = min(oracle.num_threads(), os.cpu_count() or 1)
+    full = cfg.name in FULL_ORACLE
+    rows = None if full else I.sample_rows(cfg)
+    nrows = cfg.B * cfg.H * cfg.Nq if full else int(rows.size)
+    if full:
+        pairs = cfg.visible_pairs()
+    else:
+        i = rows % cfg.Nq
+        pairs = int(np.clip(i + (cfg.Nk - cfg.Nq) + 1, 0, cfg.Nk).sum()) if cfg.causal else nrows * cfg.Nk
+    t0 = time.perf_counter()
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, rows=rows, nthreads=nthreads)
+    passes, dt = 1, time.perf_counter() - t0
+    cpu = None
+    if time_it:
+        while dt * nthreads < 20.0 and passes < 8:
+            oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, rows=rows, nthreads=nthreads)
+            passes += 1
+            dt = time.perf_counter() - t0
+        # convention flop of the rows the oracle did: 4*D per visible (query, key) pair
+        fl = 4.0 * cfg.D * pairs * passes
+        cpu = {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": nthreads, "kind": "oracle",
+               "seconds": round(dt, 3),
+               "sample": (f"all {nrows} query rows of {cfg.name}" if full else
+                          f"{nrows} of the {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name} (the seeded stratified "
+                          f"sample of 64 rows per head, {pairs:.3e} visible pairs)") + f", {passes} pass(es), fp64",
+               "flop_counted": "4*D per visible (query, key) pair of the rows computed",
+               "extrapolated_seconds_for_the_whole_workload": round(dt / passes * cfg.visible_pairs() / pairs, 1)}
+    to, tl = outputs
+    o_all = to.cpu().numpy().view(np.uint16)
+    lse_all = tl.cpu().numpy().astype(np.float64)
+    if full:
+        o, lse = I.bits_to_f64(o_all, cfg.dtype), lse_all
+    else:
+        o, lse = I.bits_to_f64(o_all.reshape(-1, cfg.D)[rows], cfg.dtype), lse_all.reshape(-1)[rows]
+    err = np.abs(o - o_ref)
+    o_ref_rounded = I.bits_to_f64(I.f32_to_bits(o_ref.astype(np.float32), cfg.dtype), cfg.dtype)
+    worst = np.unravel_index(int(np.argmax(err)), err.shape)
+    fin = np.isfinite(lse_ref)
+    parity = {"against": "fp64 oracle, " + ("every element of the timed output" if full else
+                                           f"{nrows} sampled rows of the timed output (64 per head, stratified, "
+                                           "seeded; the other rows are not oracle-checked)"),
+              "o_max_abs": float(err.max()), "o_mean_abs": float(err.mean()),
+              "lse_max_abs": float(np.abs(lse[fin] - lse_ref[fin]).max()),
+              "o_max_abs_vs_oracle_rounded_to_dtype": float(np.abs(o - o_ref_rounded).max()),
+              "elements_over_1e-2": int((err > 1e-2).sum()), "elements_checked": int(err.size),
+              "worst_element": [int(x) for x in worst] if full else
+                               {"flat_row": int(rows[worst[0]]), "d": int(worst[1])},
+              "all_lse_finite": bool(np.isfinite(lse_all).all()),
+              "tolerance": {"o_max_abs": 1e-2, "o_mean_abs": 1e-3, "lse_abs": 1e-3},
+              "pass": bool(err.max() <= 1e-2 and err.mean() <= 1e-3 and np.abs(lse[fin] - lse_ref[fin]).max() <= 1e-3)}
+    return parity, cpu
+
+
+KERNEL_OF_MODE = {0: "split", 1: "wide", 2: "wide, folded rows", 3: "streaming decode"}
+
+
+def roofline_entry(cfg, event_ms, plan):
+    flops = cfg.flops()
+    achieved = flops / (event_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), **traffic_fields(cfg.name),
+            "kernel": "fa_fwd_kernel (%s)" % KERNEL_OF_MODE[plan.mode], "avg_launch_ms": round(event_ms, 5),
+            "flops_per_launch": flops,
+            "timing": "HIP events on the launch stream around the timed steps"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # defaults: about a second of launches on the headline workload; a run of a few tens of milliseconds ends
-    # before the GPU has reached its sustained clocks and reads 10% low
-    ap.add_argument("--steps", type=int, default=None, help="timed launches (default: 20000 for C1/C2, fewer for the long ones)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed launches before (default: a quarter of --steps)")
-    ap.add_argument("--workload", default="C2", help="headline workload (C1..C5)")
+    ap.add_argument("--steps", type=int, default=None, help="timed launches (default: 20 for C5, more for the shorter ones)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed launches before (default: a quarter of --steps); the warm-up also lasts at least "
+                         "half a second whatever this says")
+    ap.add_argument("--workload", default="C5", help="headline workload (C1..C5)")
     ap.add_argument("--sliding-only", action="store_true",
                     help="time only the sliding-window workload through fa_fwd_masked (for profiling runs)")
     ap.add_argument("--projection-only", action="store_true",
@@ -389,8 +486,8 @@ def main():
                     help="with --projection-only: also time the two-stream pipeline with the exchange stand-in")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
-    ap.add_argument("--no-extra", action="store_true", help="skip the other full-size configurations")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle (baseline and parity)")
     ap.add_argument("--gpu-inputs", action="store_true",
                     help="draw the headline workload's inputs on the GPU (implies --no-cpu); for profiling runs")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -398,7 +495,7 @@ def main():
                          "for the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.steps is None:
-        args.steps = {"C1": 20000, "C2": 20000, "C3": 100, "C4": 400, "C5": 5}.get(args.workload, 50)
+        args.steps = {"C1": 20000, "C2": 20000, "C3": 200, "C4": 600, "C5": 20}.get(args.workload, 50)
         if args.decode_only:
             args.steps = 2000
         if args.sliding_only or args.projection_only:
@@ -412,6 +509,7 @@ def main():
     import numpy as np
     import torch
     from paper_2410_16663_amd import binding as fa
+    from paper_2410_16663_amd import bench_binding as fb
     from paper_2410_16663_amd import inputs as I
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -444,12 +542,13 @@ def main():
         tensors, host = device_inputs_host_recipe(cfg, torch, np, I)
     wall_ms, event_ms, outputs = time_config(cfg, tensors, args.steps, args.warmup, torch, fa)
     spread = time_config.last_spread
-    ceiling = mfma_ceiling(torch, fa, cfg.dtype, 0)
-    ceiling_random = mfma_ceiling(torch, fa, cfg.dtype, 1)
+    warm_launches = time_config.last_warmup_launches
+    ceiling = mfma_ceiling(torch, fb, cfg.dtype, 0)
+    ceiling_random = mfma_ceiling(torch, fb, cfg.dtype, 1)
     flops = cfg.flops()
     plan = fa.fa_fwd_plan(cfg.B, cfg.H, cfg.Nq, cfg.Nk, cfg.D, int(cfg.causal), cfg.dtype)
     value = flops / (wall_ms * 1e-3) / 1e12
-    achieved = flops / (event_ms * 1e-3) / 1e12
+    tensor_mib = 4 * cfg.B * cfg.H * cfg.Nq * cfg.D * 2 / 2 ** 20
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
@@ -460,68 +559,49 @@ def main():
         "mfma_only_ceiling_tflops": round(ceiling, 1), "pct_of_mfma_only_ceiling": round(100.0 * value / ceiling, 2),
         "mfma_only_ceiling_random_operands_tflops": round(ceiling_random, 1),
         "pct_of_mfma_only_ceiling_random_operands": round(100.0 * value / ceiling_random, 2),
-        "launch_time_spread": spread,
+        "launch_time_spread": spread, "warmup_launches_actually_run": warm_launches,
         "config": {"workload": cfg.describe(), "flop_convention": "4*B*H*Nq*Nk*D, halved when causal",
                    "flops_exact_visible_pairs": 4.0 * cfg.D * cfg.visible_pairs(),
-                   "accumulate": "fp32", "inputs": "N(0,1) numpy PCG64 seeds %s, resident in HBM" % (cfg.seeds,),
-                   "note": "Q,K,V,O of this workload (64 MiB) fit in the 256 MiB Infinity Cache"},
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic(cfg.name),
-                     "kernel": "fa_fwd_kernel (%s)" % {0: "split", 1: "wide", 2: "wide, folded rows", 3: "streaming decode"}[plan.mode],
-                     "avg_launch_ms": round(event_ms, 5),
-                     "flops_per_launch": flops},
+                   "accumulate": "fp32",
+                   "inputs": ("N(0,1) drawn on the GPU (torch generator)" if host is None else
+                              "N(0,1) numpy PCG64 seeds %s" % (cfg.seeds,)) + ", resident in HBM",
+                   "note": f"Q,K,V,O of this workload are {tensor_mib:.0f} MiB"
+                           + (" and fit in the 256 MiB Infinity Cache" if tensor_mib <= 256 else "")},
+        "roofline": roofline_entry(cfg, event_ms, plan),
     }
 
     if not args.no_cpu:
-        import oracle
-        q, k, v = host
-        nthreads = min(oracle.num_threads(), os.cpu_count() or 1)
-        passes = 0
-        t0 = time.perf_counter()
-        while True:   # whole passes over the workload until about 20 core-seconds are spent
-            oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
-            passes += 1
-            dt = time.perf_counter() - t0
-            if dt * nthreads >= 20.0 or passes >= 8:
-                break
-        out["cpu_baseline"] = {"value": round(passes * flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": nthreads,
-                               "kind": "oracle", "seconds": round(dt, 3),
-                               "sample": f"all {cfg.B * cfg.H * cfg.Nq} query rows of {cfg.name}, "
-                                         f"{passes} full pass(es), fp64"}
-        # the timed output against the oracle (whole workload), and against the oracle rounded to the output
-        # format, so that a miss by one rounding step can be told from a wrong result
-        o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, nthreads=nthreads)
-        to, tl = outputs
-        o = I.bits_to_f64(to.cpu().numpy().view(np.uint16), cfg.dtype)
-        lse = tl.cpu().numpy().astype(np.float64)
-        err = np.abs(o - o_ref)
-        o_ref_rounded = I.bits_to_f64(I.f32_to_bits(o_ref.astype(np.float32), cfg.dtype), cfg.dtype)
-        worst = np.unravel_index(int(np.argmax(err)), err.shape)
-        fin = np.isfinite(lse_ref)
-        out["parity"] = {"against": "fp64 oracle, every element of the timed output",
-                         "o_max_abs": float(err.max()), "o_mean_abs": float(err.mean()),
-                         "lse_max_abs": float(np.abs(lse[fin] - lse_ref[fin]).max()),
-                         "o_max_abs_vs_oracle_rounded_to_dtype": float(np.abs(o - o_ref_rounded).max()),
-                         "elements_over_1e-2": int((err > 1e-2).sum()), "worst_element_bhid": [int(x) for x in worst],
-                         "tolerance": {"o_max_abs": 1e-2, "o_mean_abs": 1e-3, "lse_abs": 1e-3}}
+        out["parity"], out["cpu_baseline"] = oracle_leg(cfg, host, outputs, np, I, True)
 
     if not args.no_extra:
         extra = {}
+        del outputs
         if cfg.name == "C2":
             extra["C2_from_hbm"] = rotating_entry(cfg, torch, fa, 8, 8000, 2000)
-        for name in ("C3", "C4", "C5"):
+        for name in ("C3", "C2", "C4", "C5"):
             if name == cfg.name:
                 continue
             c = I.CONFIGS[name]
             del tensors
             torch.cuda.empty_cache()
-            tensors = device_inputs_on_gpu(c, torch)
-            steps = {"C3": 30, "C4": 100, "C5": 3}[name]   # 0.1-0.3 s each: long enough for sustained clocks
-            w_ms, e_ms, _ = time_config(c, tensors, steps, max(1, steps // 10), torch, fa)
-            tf = c.flops() / (e_ms * 1e-3) / 1e12
-            extra[name] = {"workload": c.describe(), "ms_per_launch": round(e_ms, 4), "tflops": round(tf, 2),
-                           "pct_of_mfma_peak": round(100.0 * tf / MFMA_PEAK_TFLOPS, 2), "steps": steps,
-                           "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)"}
+            # C2 and C3 (the other causal D = 128 configurations): the seeded host recipe, so that their outputs can
+            # be checked against the oracle too; C4 / C5 as extras: drawn on the GPU, timing only
+            check = name in ("C2", "C3") and not args.no_cpu
+            if check:
+                tensors, h = device_inputs_host_recipe(c, torch, np, I)
+            else:
+                tensors, h = device_inputs_on_gpu(c, torch), None
+            steps = {"C2": 20000, "C3": 100, "C4": 300, "C5": 5}[name]   # 0.3-1 s each
+            w_ms, e_ms, outs = time_config(c, tensors, steps, max(1, steps // 10), torch, fa)
+            pl = fa.fa_fwd_plan(c.B, c.H, c.Nq, c.Nk, c.D, int(c.causal), c.dtype)
+            extra[name] = {"workload": c.describe(), "ms_per_launch": round(e_ms, 5),
+                           "tflops": round(c.flops() / (e_ms * 1e-3) / 1e12, 2), "steps": steps,
+                           "inputs": "N(0,1) numpy PCG64 seeds %s" % (c.seeds,) if check
+                                     else "N(0,1) drawn on the GPU (torch generator, same seeds)",
+                           "roofline": roofline_entry(c, e_ms, pl)}
+            if check:
+                extra[name]["parity"], _ = oracle_leg(c, h, outs, np, I, False)
+            del outs, h
         del tensors
         torch.cuda.empty_cache()
         extra["DEC"] = decode_entry(I, torch, fa, 500, 50)

@@ -28,6 +28,7 @@ extern "C" {
 #define FA_ERR_WORKSPACE -8 /* fa_fwd_splitkv: workspace NULL or smaller than fa_fwd_splitkv_plan reports */
 #define FA_ERR_NSPLIT   -9 /* fa_fwd_splitkv: nsplit > 1024 */
 #define FA_ERR_MASK     -10 /* fa_fwd_masked: prefix < 0, or a key count outside 0..Nk */
+#define FA_ERR_OPTION   -11 /* fa_set_option: unknown option, or a value it does not take */
 
 #define FA_DTYPE_F16  0 /* IEEE binary16 */
 #define FA_DTYPE_BF16 1 /* bfloat16 */
@@ -78,11 +79,11 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256; for causal problems with
  * Nq > 768: WIDE_FOLD when Nq <= 4096, W <= 1024 and the last round of 256 workgroups is at
  * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); WIDE otherwise.
- * The environment variable FA_FWD_MODE=split|wide|fold overrides the choice (tests, tuning).
+ * fa_set_option(FA_OPT_FWD_MODE, ...) overrides the choice (tests, tuning).
  * Nq = 1 (one decoding step) takes none of these: FA_MODE_STREAM, the register-streaming kernel
  * described at fa_fwd_splitkv, one workgroup per (batch, head) -- full speed when B*H fills the
  * chip; with fewer heads fa_fwd_splitkv, which has a workspace to split the cache over, is the
- * call to make.  FA_DECODE=mfma keeps Nq = 1 on the tile kernels.
+ * call to make.  fa_set_option(FA_OPT_DECODE_KERNEL, 1) keeps Nq = 1 on the tile kernels.
  */
 #define FA_MODE_SPLIT 0
 #define FA_MODE_WIDE  1
@@ -117,8 +118,8 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
  * kernel merges them: lse = logsumexp over runs, o = sum_runs exp(lse_run - lse) o_run.
  * Bound by reading K and V once from HBM.  Nq = 1, the decoding step proper, runs a kernel of its
  * own that streams K and V through registers (one multiply-add per element leaves the matrix
- * cores nothing to reuse) and keeps the probabilities in fp32; the environment variable
- * FA_DECODE=mfma sends it through the tile kernel instead (tests, tuning).
+ * cores nothing to reuse) and keeps the probabilities in fp32; fa_set_option(FA_OPT_DECODE_KERNEL, 1)
+ * sends it through the tile kernel instead (tests, tuning).
  *
  *   nsplit          : > 0: number of runs (clamped to the number of 64-key tiles, at most 1024);
  *                     <= 0: the library picks (256 workgroups at D = 128 and for a single query,
@@ -177,10 +178,10 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
  * communication by enqueueing it on another stream behind an event recorded after this call.
  * Calls for different blocks are independent.  Error behaviour as for fa_fwd.  The GEMM's
  * workgroup tile is 256 tokens x 256 outputs when that still gives each of the 256 compute units
- * a workgroup (B * ceil(row_count/256) * N/256 >= 256), else 128 x 256; the environment variable
- * FA_LINEAR_TILE=128|256 overrides (tests, tuning).  The tiles are dealt to the XCDs in panels of
- * a few row tiles so that each L2 fetches about as many bytes of o as of w; FA_LINEAR_PANEL=<row
- * tiles per panel> overrides that too (the order changes no result).
+ * a workgroup (B * ceil(row_count/256) * N/256 >= 256), else 128 x 256; fa_set_option(FA_OPT_LINEAR_TILE,
+ * 128 | 256) overrides (tests, tuning).  The tiles are dealt to the XCDs in panels of
+ * a few row tiles so that each L2 fetches about as many bytes of o as of w; fa_set_option(
+ * FA_OPT_LINEAR_PANEL, row tiles per panel) overrides that too (the order changes no result).
  *
  * fa_attn_linear -- every block in order on one stream: blocks of rows_per_block rows, the first
  * one half that size (nothing can overlap with the first block); rows_per_block <= 0: one block.
@@ -229,7 +230,7 @@ typedef struct fa_mask {
  * rows' windows touch.  Nq = 1 (a decoding step over caches of different lengths, or with a
  * sliding window) runs the register-streaming kernel of fa_fwd_splitkv instead, one workgroup
  * per (batch, head), which walks the prefix and the window as runs of consecutive keys
- * (FA_DECODE=mfma keeps the tile kernel).
+ * (fa_set_option(FA_OPT_DECODE_KERNEL, 1) keeps the tile kernel).
  */
 int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *lse,
                   int B, int H, int Nq, int Nk, int D, float scale, const fa_mask_t *mask, int dtype,
@@ -264,11 +265,14 @@ int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float
  *   multiple of 64).  Returns
  *   FA_TILE_SKIP (certainly nothing visible), FA_TILE_FULL (certainly everything visible, and all
  *   64 keys exist), FA_TILE_PARTIAL (anything else), or a negative FA_ERR_* code.
- * fa_mask_tile_walk: the 64-key tiles a workgroup owning rows row_first..row_last visits, in
- *   order: tiles 0 .. *prefix_tiles-1, then the cw = *count - *prefix_tiles consecutive tiles from
- *   *window_first_tile on, starting with tile *window_first_tile + *window_rotation and wrapping
- *   around (so that co-resident workgroups with shifted windows read the same tile at the same
- *   time).  Every tile holding a key visible to one of the rows is among them.
+ * fa_mask_tile_walk: the 64-key tiles a workgroup owning rows row_first..row_last visits, in the
+ *   order the kernel visits them (position j -> tile index, by the kernel's own mapping): the tiles
+ *   holding prefix keys, then the consecutive tiles the rows' windows touch, a long window run
+ *   starting somewhere in its middle and wrapping around (so that co-resident workgroups with
+ *   shifted windows read the same tile at the same time).  *count (HOST pointer) receives the
+ *   length of the walk; the first min(*count, capacity) tile indices are written to `tiles` (HOST
+ *   array of `capacity` ints; NULL with capacity 0 just asks for the length).  Every tile holding a
+ *   key visible to one of the rows is among them.
  * fa_mask_interior_run: within the walk of the workgroup owning rows wg_row_first..wg_row_last, the
  *   positions [*first, *first + *count) that the wave owning rows row_first..row_last processes
  *   without any check: each of those tiles is FA_TILE_FULL for the wave and the tile at the next
@@ -280,22 +284,32 @@ int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float
 int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk,
                        int row_first, int row_last, int key_first);
 int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
-                      int *prefix_tiles, int *window_first_tile, int *count, int *window_rotation);
+                      int *tiles, int capacity, int *count);
 int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int wg_row_first, int wg_row_last,
                          int row_first, int row_last, int *first, int *count);
 
 /*
- * fa_mfma_probe -- measurement aid: enqueues a kernel that issues nothing but independent
- * v_mfma_f32_32x32x16 instructions of `dtype` (256 workgroups of 8 waves, `iters` x 4 instructions
- * per wave) and reports the floating-point operations it performs in *flops (HOST pointer).  Timed
- * by the caller, it gives the matrix throughput the chip sustains under its power limit -- the
- * practical ceiling to quote beside the nominal peak.  `operands`: 0 = one pair of operands with
- * a few low bits set, the same for every instruction (hardly any switching: the friendliest case
- * for the power limit); 1 = four pairs of pseudo-random operands taken in turn (signs and
- * mantissas toggle from instruction to instruction, as with real data).  `scratch`: DEVICE
- * pointer to one float (never written in practice).  1 <= iters <= 2^24.
+ * fa_set_option -- test and tuning hook: overrides a choice the library otherwise makes from the
+ * problem's shape (the work decompositions described at fa_plan_t, fa_fwd_splitkv and
+ * fa_attn_linear_block).  Process-wide; every entry point reads each option once per call, so a
+ * change made while another thread is inside a call applies to that thread's next call.  No
+ * environment variable is read anywhere in the library.
+ *
+ *   FA_OPT_FWD_MODE      : FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD (causal problems only; WIDE
+ *                          otherwise) or FA_AUTO
+ *   FA_OPT_DECODE_KERNEL : 0 or FA_AUTO: Nq = 1 runs the register-streaming kernel; 1: the tile kernels
+ *   FA_OPT_LINEAR_TILE   : 128, 256 or FA_AUTO: token rows per workgroup tile of the projection
+ *   FA_OPT_LINEAR_PANEL  : >= 1 or FA_AUTO: row tiles per panel of the projection's tile order
+ *
+ * Returns the option's previous value (FA_AUTO = -1 if it was never set), or FA_ERR_OPTION for an
+ * unknown option or a value outside the list above (nothing is changed then).
  */
-int fa_mfma_probe(int dtype, int operands, int iters, float *scratch, long long *flops, void *stream);
+#define FA_AUTO (-1)
+#define FA_OPT_FWD_MODE      0
+#define FA_OPT_DECODE_KERNEL 1
+#define FA_OPT_LINEAR_TILE   2
+#define FA_OPT_LINEAR_PANEL  3
+int fa_set_option(int option, int value);
 
 /* static, never-freed description of an FA_ERR_* code */
 const char *fa_strerror(int code);

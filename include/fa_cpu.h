@@ -69,18 +69,6 @@ int fa_cpu_decode(const void *q, const void *k, const void *v, void *o, float *l
    FA_CPU_FORCE_SCALAR=1 turns the AVX-512 path off, for tests) */
 int fa_cpu_has_avx512(void);
 
-/*
- * fa_cpu_stream_read -- measurement aid, the yardstick for fa_cpu_decode: `nthreads` threads (<= 0: the
- * runtime's default) each add up a contiguous share of the 64-byte lines of `buf` (HOST pointer, `bytes` >=
- * 64, a tail shorter than a line is left out), `reps` times over; *gb_per_s receives the bytes read per
- * second in units of 1e9, *checksum the sum of the 64-bit words modulo 2^64 times `reps` (so that the reads
- * cannot be optimised away, and so that a test can check them).  Same AVX-512 / plain C choice as
- * fa_cpu_decode.  Decoding-step attention reads every byte of K and V once and does little else: what this
- * loop reaches over a buffer much larger than the caches is the ceiling for it on the machine at hand.
- */
-int fa_cpu_stream_read(const void *buf, long long bytes, int nthreads, int reps, double *gb_per_s,
-                       unsigned long long *checksum);
-
 #ifdef __cplusplus
 }
 #endif

@@ -23,6 +23,12 @@ FA_ERR_LAUNCH = -7
 FA_ERR_WORKSPACE = -8
 FA_ERR_NSPLIT = -9
 FA_ERR_MASK = -10
+FA_ERR_OPTION = -11
+FA_AUTO = -1
+FA_OPT_FWD_MODE = 0
+FA_OPT_DECODE_KERNEL = 1
+FA_OPT_LINEAR_TILE = 2
+FA_OPT_LINEAR_PANEL = 3
 FA_TILE_SKIP = 0
 FA_TILE_FULL = 1
 FA_TILE_PARTIAL = 2
@@ -36,7 +42,7 @@ FA_MODE_STREAM = 3
 # every symbol include/fa.h declares
 EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
            "fa_attn_linear", "fa_mask_tile_class",
-           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_mfma_probe", "fa_strerror", "fa_version", "fa_last_hip_error",
+           "fa_mask_tile_walk", "fa_mask_interior_run", "fa_set_option", "fa_strerror", "fa_version", "fa_last_hip_error",
            "fa_decode_masked")
 
 _lib = None
@@ -126,11 +132,11 @@ def load() -> ctypes.CDLL:
         lib.fa_mask_tile_class.restype = ctypes.c_int
         lib.fa_mask_tile_class.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 6
         lib.fa_mask_tile_walk.restype = ctypes.c_int
-        lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ip, ip, ip]
+        lib.fa_mask_tile_walk.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 5 + [ip, ctypes.c_int, ip]
         lib.fa_mask_interior_run.restype = ctypes.c_int
         lib.fa_mask_interior_run.argtypes = [ctypes.POINTER(FaMask)] + [ctypes.c_int] * 7 + [ip, ip]
-        lib.fa_mfma_probe.restype = ctypes.c_int
-        lib.fa_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_longlong), vp]
+        lib.fa_set_option.restype = ctypes.c_int
+        lib.fa_set_option.argtypes = [ctypes.c_int, ctypes.c_int]
         lib.fa_strerror.restype = ctypes.c_char_p
         lib.fa_strerror.argtypes = [ctypes.c_int]
         lib.fa_version.restype = ctypes.c_int
@@ -275,13 +281,16 @@ def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last,
 def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last):
     """fa_mask_tile_walk of include/fa.h (host only): the list of tile indices, in the order walked."""
     m = _mask(left, right, prefix, None)
-    np_, base, count, rot = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    rc = load().fa_mask_tile_walk(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last),
-                                  ctypes.byref(np_), ctypes.byref(base), ctypes.byref(count), ctypes.byref(rot))
+    count = ctypes.c_int()
+    args = (ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last))
+    rc = load().fa_mask_tile_walk(*args, None, 0, ctypes.byref(count))
     if rc != FA_OK:
         raise FaError(rc)
-    cw = count.value - np_.value
-    return list(range(np_.value)) + [base.value + (i + rot.value) % cw for i in range(cw)]
+    tiles = (ctypes.c_int * max(count.value, 1))()
+    rc = load().fa_mask_tile_walk(*args, tiles, count.value, ctypes.byref(count))
+    if rc != FA_OK:
+        raise FaError(rc)
+    return list(tiles[:count.value])
 
 
 def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_row_last, row_first, row_last):
@@ -296,14 +305,12 @@ def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_r
     return first.value, count.value
 
 
-def fa_mfma_probe(dtype, operands, iters, scratch, stream=0) -> int:
-    """fa_mfma_probe of include/fa.h: enqueue the matrix-only kernel, return the flop it performs."""
-    flops = ctypes.c_longlong()
-    rc = load().fa_mfma_probe(int(dtype), int(operands), int(iters), _addr(scratch), ctypes.byref(flops),
-                              _addr(stream))
-    if rc != FA_OK:
+def fa_set_option(option: int, value: int) -> int:
+    """fa_set_option of include/fa.h: returns the previous value; raises FaError for an unknown option or value."""
+    rc = load().fa_set_option(int(option), int(value))
+    if rc == FA_ERR_OPTION:
         raise FaError(rc)
-    return flops.value
+    return rc
 
 
 def fa_strerror(code: int) -> str:

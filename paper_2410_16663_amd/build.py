@@ -15,7 +15,7 @@ HDR = os.path.join(os.path.dirname(HERE), "include", "fa.h")
 # fragments of the one translation unit, included by fa_fwd.hip
 FRAGMENTS = [os.path.join(HERE, "csrc", n) for n in (
     "fa_types.inc", "fa_mask.inc", "fa_device.inc", "fa_attention_kernel.inc", "fa_linear_kernel.inc",
-    "fa_probe_kernel.inc", "fa_decode_kernels.inc")]
+    "fa_decode_kernels.inc")]
 LIB = os.path.join(HERE, "libfa.so")
 
 HIPCC_FLAGS = [
@@ -106,6 +106,30 @@ def build_cpu(force: bool = True) -> str:
     return CPU_LIB
 
 
+BENCH_SRC = os.path.join(HERE, "csrc", "fa_bench.hip")
+BENCH_LIB = os.path.join(HERE, "libfa_bench.so")
+BENCH_CPU_SRC = os.path.join(HERE, "csrc", "fa_bench_cpu.c")
+BENCH_CPU_LIB = os.path.join(HERE, "libfa_bench_cpu.so")
+
+
+def build_bench(force: bool = True):
+    """Compile the benchmark's measurement aids (include/fa_bench.h): libfa_bench.so with hipcc (the matrix-only
+    probe kernel) and libfa_bench_cpu.so with gcc (the host streaming-read yardstick)."""
+    out = []
+    for src, lib, cmd in (
+            (BENCH_SRC, BENCH_LIB, [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")]
+             + [f for f in HIPCC_FLAGS if not f.startswith("-Rpass")]),
+            (BENCH_CPU_SRC, BENCH_CPU_LIB, [os.environ.get("CC", "gcc"), "-O3", "-fopenmp", "-shared", "-fPIC", "-Wall",
+                                            "-Wextra"])):
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+            r = subprocess.run(cmd + [src, "-o", lib], capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"building {lib} failed:\n{r.stdout}\n{r.stderr}")
+        out.append(lib)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
     print(build_cpu(force=True))
+    print(build_bench(force=True))

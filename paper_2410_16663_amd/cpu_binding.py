@@ -20,7 +20,7 @@ FA_CPU_ERR_SCALE = -5
 FA_CPU_ERR_NOMEM = -8
 
 # every symbol include/fa_cpu.h declares
-EXPORTS = ("fa_coop_plan_bytes", "fa_coop_plan_fp16", "fa_cpu_decode", "fa_cpu_has_avx512", "fa_cpu_stream_read")
+EXPORTS = ("fa_coop_plan_bytes", "fa_coop_plan_fp16", "fa_cpu_decode", "fa_cpu_has_avx512")
 
 _lib = None
 
@@ -49,9 +49,6 @@ def load() -> ctypes.CDLL:
                                                                                   ctypes.c_int]
         lib.fa_cpu_has_avx512.restype = ctypes.c_int
         lib.fa_cpu_has_avx512.argtypes = []
-        lib.fa_cpu_stream_read.restype = ctypes.c_int
-        lib.fa_cpu_stream_read.argtypes = [vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int,
-                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_ulonglong)]
         _lib = lib
     return _lib
 
@@ -101,14 +98,3 @@ def fa_cpu_decode(q, k, v, o, lse, B, H, Nk, D, scale, dtype, nthreads=0) -> Non
 
 def fa_cpu_has_avx512() -> bool:
     return bool(load().fa_cpu_has_avx512())
-
-
-def fa_cpu_stream_read(buf, nbytes, nthreads=0, reps=1):
-    """fa_cpu_stream_read of include/fa_cpu.h: (GB/s, checksum) of `reps` threaded passes over a host buffer."""
-    gbs = ctypes.c_double()
-    chk = ctypes.c_ulonglong()
-    rc = load().fa_cpu_stream_read(_addr(buf), int(nbytes), int(nthreads), int(reps), ctypes.byref(gbs),
-                                   ctypes.byref(chk))
-    if rc != FA_CPU_OK:
-        raise FaCpuError(rc)
-    return gbs.value, chk.value

@@ -19,8 +19,8 @@
 //    entry points fa_attn_linear_block / fa_attn_linear.
 //  * fa_mask.inc -- descriptor masks: tile classification and walk, shared by the kernel and the host entry
 //    points fa_mask_*.
-//  * fa_types.inc, fa_device.inc, fa_probe_kernel.inc -- vector types and parameter block; device helpers
-//    (LDS swizzles, global-to-LDS load, cross-half exchange); the matrix-only ceiling probe.
+//  * fa_types.inc, fa_device.inc -- vector types and parameter block; device helpers (LDS swizzles,
+//    global-to-LDS load, cross-half exchange).
 //  * this file -- the host side: argument checks, choice of decomposition, launch shapes, the C ABI.
 //
 // gfx950 mapping common to all variants of the attention kernel (this library's own design):
@@ -45,6 +45,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -57,7 +58,6 @@ namespace {
 #include "fa_device.inc"
 #include "fa_attention_kernel.inc"
 #include "fa_linear_kernel.inc"
-#include "fa_probe_kernel.inc"
 #include "fa_decode_kernels.inc"
 
 template <int DT, int D, bool CAUSAL, bool WIDE>
@@ -108,7 +108,9 @@ hipError_t launch_decode_masked(const FaParams &p, int heads, hipStream_t stream
 
 thread_local int g_last_hip_error = 0;
 
-
+// fa_set_option's values (FA_AUTO: the library chooses).  Every entry point reads each of them at most once per call.
+std::atomic<int> g_options[4] = {{FA_AUTO}, {FA_AUTO}, {FA_AUTO}, {FA_AUTO}};
+int option(int which) { return g_options[which].load(std::memory_order_relaxed); }
 
 // Shape checks shared by fa_fwd and fa_fwd_plan; everything here runs before any HIP call.
 int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
@@ -122,12 +124,9 @@ int check_shape(int B, int H, int Nq, int Nk, int D, int dtype) {
     return FA_OK;
 }
 
-// One query row per head goes through the streaming kernel (FA_DECODE=mfma keeps the tile kernel: tests, tuning)
-bool use_streaming_decode(int Nq) {
-    if (Nq != 1) return false;
-    const char *env = getenv("FA_DECODE");
-    return !(env && !strcmp(env, "mfma"));
-}
+// One query row per head goes through the streaming kernel (FA_OPT_DECODE_KERNEL = 1 keeps the tile kernel:
+// tests, tuning)
+bool use_streaming_decode(int Nq) { return Nq == 1 && option(FA_OPT_DECODE_KERNEL) != 1; }
 
 // Work decomposition for a problem, W = B * H * ceil(Nq / 256) being the number of 256-row workgroups
 // (the chip has 256 compute units and a D = 128 workgroup fills one).  From a sweep of forced modes
@@ -141,12 +140,11 @@ bool use_streaming_decode(int Nq) {
 //  * causal, few rounds of long chains otherwise (W < 640 up to Nq = 4096, W < 384 beyond):
 //    FA_MODE_SPLIT, whose shorter chains matter more than its extra K/V traffic;
 //  * otherwise FA_MODE_WIDE: with many rounds the heavy-first dynamic dispatch evens out the triangle.
-// The environment variable FA_FWD_MODE ("split" / "wide" / "fold") overrides.
+// fa_set_option(FA_OPT_FWD_MODE, ...) overrides.
 int choose_mode(int B, int H, int Nq, int causal) {
-    const char *env = getenv("FA_FWD_MODE");
-    if (env && !strcmp(env, "split")) return FA_MODE_SPLIT;
-    if (env && !strcmp(env, "wide")) return FA_MODE_WIDE;
-    if (env && !strcmp(env, "fold")) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
+    const int forced = option(FA_OPT_FWD_MODE);
+    if (forced == FA_MODE_SPLIT || forced == FA_MODE_WIDE) return forced;
+    if (forced == FA_MODE_WIDE_FOLD) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
     const long long nqt = ((long long)Nq + 255) / 256;
     const long long W = (long long)B * H * nqt;
     if (W < 256) return FA_MODE_SPLIT;
@@ -604,19 +602,17 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
         lp.rows = row_count;
         lp.n_tiles = N / 256;
         // 256-row tiles (less LDS traffic per matrix instruction, twice the work per barrier) when they still
-        // give every compute unit a workgroup; FA_LINEAR_TILE=128|256 overrides (tests, tuning)
+        // give every compute unit a workgroup; FA_OPT_LINEAR_TILE overrides (tests, tuning)
         int BM = (long long)B * ((row_count + 255) / 256) * lp.n_tiles >= 256 ? 256 : 128;
-        if (const char *env = getenv("FA_LINEAR_TILE")) BM = !strcmp(env, "256") ? 256 : (!strcmp(env, "128") ? 128 : BM);
+        if (const int forced = option(FA_OPT_LINEAR_TILE); forced == 128 || forced == 256) BM = forced;
         lp.mt_per_b = (row_count + BM - 1) / BM;
         const long long tiles = (long long)B * lp.mt_per_b * lp.n_tiles;
         if (tiles > 0x7ffffff0LL) return FA_ERR_SHAPE;
         lp.ntile_total = (int)tiles;
         lp.per_xcd = (int)((tiles + 7) / 8);
         lp.panel = linear_panel(lp.per_xcd, BM, B * lp.mt_per_b);
-        if (const char *env = getenv("FA_LINEAR_PANEL")) {   // tests, tuning
-            const int v = atoi(env);
-            if (v >= 1) lp.panel = v < B * lp.mt_per_b ? v : B * lp.mt_per_b;
-        }
+        if (const int v = option(FA_OPT_LINEAR_PANEL); v >= 1)   // tests, tuning
+            lp.panel = v < B * lp.mt_per_b ? v : B * lp.mt_per_b;
         hipError_t e;
         switch ((dtype << 1) | (D == 128)) {
             case 0: e = launch_linear<0, 64>(lp, BM, st); break;
@@ -657,18 +653,16 @@ int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int ro
     return tile_class(row_tiles(g, row_first, row_last), key_first / BN);
 }
 
-int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last,
-                      int *prefix_tiles, int *window_first_tile, int *count, int *window_rotation) {
-    if (!prefix_tiles || !window_first_tile || !count || !window_rotation) return FA_ERR_NULL;
+int fa_mask_tile_walk(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last, int *tiles,
+                      int capacity, int *count) {
+    if (!count || (capacity > 0 && !tiles)) return FA_ERR_NULL;
     MaskGeom g;
     const int rc = mask_geometry(mask, kv_len, Nq, Nk, &g);
     if (rc != FA_OK) return rc;
-    if (row_first < 0 || row_last < row_first || row_last >= Nq) return FA_ERR_SHAPE;
+    if (row_first < 0 || row_last < row_first || row_last >= Nq || capacity < 0) return FA_ERR_SHAPE;
     const TileSeq sq = tile_sequence(g, row_first, row_last);
-    *prefix_tiles = sq.np;
-    *window_first_tile = sq.base;
     *count = sq.count;
-    *window_rotation = sq.rot;
+    for (int j = 0; j < sq.count && j < capacity; ++j) tiles[j] = sq.tile(j);   // the kernel's own position -> tile map
     return FA_OK;
 }
 
@@ -686,27 +680,17 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
     return FA_OK;
 }
 
-int fa_mfma_probe(int dtype, int operands, int iters, float *scratch, long long *flops, void *stream) {
-    if (!scratch || !flops) return FA_ERR_NULL;
-    if (dtype != FA_DTYPE_F16 && dtype != FA_DTYPE_BF16) return FA_ERR_DTYPE;
-    if (operands != 0 && operands != 1) return FA_ERR_SHAPE;
-    if (iters <= 0 || iters > (1 << 24)) return FA_ERR_SHAPE;
-    if ((uintptr_t)scratch & 3) return FA_ERR_ALIGN;
-    const int grid = 256;                                   // one workgroup of 8 waves per compute unit
-    hipStream_t st = (hipStream_t)stream;
-    switch ((dtype << 1) | operands) {
-        case 0: hipLaunchKernelGGL((fa_mfma_probe_kernel<0, false>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
-        case 1: hipLaunchKernelGGL((fa_mfma_probe_kernel<0, true>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
-        case 2: hipLaunchKernelGGL((fa_mfma_probe_kernel<1, false>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
-        default: hipLaunchKernelGGL((fa_mfma_probe_kernel<1, true>), dim3(grid), dim3(512), 0, st, scratch, iters); break;
+int fa_set_option(int opt, int value) {
+    bool ok = value == FA_AUTO;
+    switch (opt) {
+        case FA_OPT_FWD_MODE: ok = ok || value == FA_MODE_SPLIT || value == FA_MODE_WIDE || value == FA_MODE_WIDE_FOLD; break;
+        case FA_OPT_DECODE_KERNEL: ok = ok || value == 0 || value == 1; break;
+        case FA_OPT_LINEAR_TILE: ok = ok || value == 128 || value == 256; break;
+        case FA_OPT_LINEAR_PANEL: ok = ok || value >= 1; break;
+        default: return FA_ERR_OPTION;
     }
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        g_last_hip_error = (int)e;
-        return FA_ERR_LAUNCH;
-    }
-    *flops = (long long)grid * 8 * iters * 4 * (2LL * 32 * 32 * 16);
-    return FA_OK;
+    if (!ok) return FA_ERR_OPTION;
+    return g_options[opt].exchange(value, std::memory_order_relaxed);
 }
 
 const char *fa_strerror(int code) {
@@ -722,6 +706,7 @@ const char *fa_strerror(int code) {
         case FA_ERR_WORKSPACE: return "workspace is NULL or smaller than fa_fwd_splitkv_plan reports";
         case FA_ERR_NSPLIT: return "nsplit exceeds 1024";
         case FA_ERR_MASK: return "mask descriptor: prefix must be >= 0 and a key count within 0..Nk";
+        case FA_ERR_OPTION: return "fa_set_option: unknown option, or a value it does not take";
         default: return "unknown error code";
     }
 }

@@ -127,19 +127,36 @@ def bf16_half_ulp(x):
     return 2.0 ** (np.floor(np.log2(ax)) - 8)
 
 
-def check_against_oracle(o_bits, lse, o_ref, lse_ref, dtype, label=""):
-    """Assert the stated tolerances. o_bits/o_ref and lse/lse_ref have matching shapes."""
+# elements that needed the bf16 allowance (see check_against_oracle) since the process started, per label
+allowance_used = {}
+
+
+def check_against_oracle(o_bits, lse, o_ref, lse_ref, dtype, label="", named_config=False):
+    """Assert the stated tolerances (O max-abs 1e-2, O mean-abs 1e-3, lse 1e-3). o_bits/o_ref and lse/lse_ref
+    have matching shapes.
+
+    One allowance, and only outside the named workloads (``named_config=False``): a bf16 output whose exact
+    value is 4 or more in magnitude cannot meet 1e-2 by construction -- half a unit in the last place of bf16 is
+    0.0156 there -- so such an element may be off by its half-ulp plus 5e-3.  Everything below 4 in magnitude,
+    every fp16 element, and every element of a named workload (``named_config=True``: C1..C5, DEC, SWA, LIN)
+    must meet the plain 1e-2.  The number of elements that used the allowance is returned, printed, and kept
+    in ``allowance_used``."""
     o = I.bits_to_f64(o_bits, dtype).reshape(o_ref.shape)
     assert np.isfinite(o).all(), f"{label}: non-finite or unwritten output"
     err = np.abs(o - o_ref)
     tol = np.full_like(err, O_MAX_ABS)
-    if dtype == I.BF16:
-        # a bf16 result cannot be closer to the oracle than its own rounding allows: where half an
-        # ulp of the output format is a large part of the budget, allow it on top of a 5e-3 budget
-        tol = np.maximum(tol, bf16_half_ulp(o_ref) + 5e-3)
+    n_allow = 0
+    if dtype == I.BF16 and not named_config:
+        big = np.abs(o_ref) >= 4.0
+        if big.any():
+            tol = np.where(big, bf16_half_ulp(o_ref) + 5e-3, tol)
+            n_allow = int((big & (err > O_MAX_ABS)).sum())
     worst = np.unravel_index(np.argmax(err - tol), err.shape)
-    assert (err <= tol).all(), (f"{label}: O max-abs {err.max():.3e}; worst at {worst}: got {o[worst]!r} "
-                                f"want {o_ref[worst]!r} (tol {tol[worst]:.3e})")
+    assert (err <= tol).all(), (f"{label}: O max-abs {err.max():.3e}; {int((err > tol).sum())} element(s) over; worst at "
+                                f"{worst}: got {o[worst]!r} want {o_ref[worst]!r} (tol {tol[worst]:.3e})")
+    if n_allow:
+        allowance_used[label] = allowance_used.get(label, 0) + n_allow
+        print(f"{label}: {n_allow} bf16 element(s) of magnitude >= 4 used the half-ulp allowance", flush=True)
     assert err.mean() <= O_MEAN_ABS, f"{label}: O mean-abs {err.mean():.3e}"
     lse = np.asarray(lse, dtype=np.float64).reshape(lse_ref.shape)
     inf = np.isneginf(lse_ref)
@@ -149,4 +166,4 @@ def check_against_oracle(o_bits, lse, o_ref, lse_ref, dtype, label=""):
     if lerr.size:
         assert lerr.max() <= LSE_ABS, f"{label}: lse max-abs {lerr.max():.3e}"
     return dict(o_max=float(err.max()), o_mean=float(err.mean()), lse_max=float(lerr.max()) if lerr.size else 0.0,
-                n_over_1e2=int((err > O_MAX_ABS).sum()))
+                n_over_1e2=int((err > O_MAX_ABS).sum()), n_allowance=n_allow)

@@ -1,5 +1,5 @@
 /*
- * Driver for the sanitizer build of the host-side C code (the oracle and libfa_cpu's sources): runs small
+ * Driver for the sanitizer build of the host-side C code (the oracle, libfa_cpu's and libfa_bench_cpu's sources): runs small
  * cases of every exported function under AddressSanitizer and UndefinedBehaviorSanitizer.  Exit code 0 = clean.
  * Built and run by tests/test_sanitizers.py; not part of any library.
  */
@@ -18,7 +18,7 @@ int fa_oracle_attn_linear(const uint16_t *, const uint16_t *, const uint16_t *, 
 int fa_coop_plan_bytes(double, double, double, double, double, int, int, int *, int *);
 int fa_coop_plan_fp16(double, int, int, long long, long long, long long, long long, long long, long long, int *, int *);
 int fa_cpu_decode(const void *, const void *, const void *, void *, float *, int, int, int, int, float, int, int);
-int fa_cpu_stream_read(const void *, long long, int, int, double *, unsigned long long *);
+int fa_cpu_stream_read(const void *, long long, int, int, int, double *, unsigned long long *);
 
 static uint32_t rng_state = 12345u;
 static uint16_t rand_half(void) {               /* a finite fp16 / bf16 pattern of moderate size */
@@ -63,7 +63,10 @@ int main(void) {
             /* the streaming-read yardstick over a buffer that does not end on a 64-byte line */
             double gbs;
             unsigned long long chk;
-            CHECK(fa_cpu_stream_read(k1, (long long)sizeof(uint16_t) * B * H * 1000 * 64 - 6, 5, 2, &gbs, &chk));
+            {
+                const char *fs = getenv("FA_CPU_FORCE_SCALAR");
+                CHECK(fa_cpu_stream_read(k1, (long long)sizeof(uint16_t) * B * H * 1000 * 64 - 6, 5, 2, fs && fs[0] == '1', &gbs, &chk));
+            }
             free(q); free(k); free(v); free(w); free(o); free(lse); free(p); free(y);
             free(q1); free(k1); free(v1); free(o1); free(l1);
         }

@@ -6,6 +6,7 @@ import re
 import pytest
 
 from paper_2410_16663_amd import binding as fa
+import options
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -30,11 +31,11 @@ def test_library_exports_every_declared_symbol(lib):
 def test_version_and_error_strings(lib):
     assert fa.fa_version() >= 100
     seen = set()
-    for code in range(0, -11, -1):
+    for code in range(0, -12, -1):
         s = fa.fa_strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 11
+    assert len(seen) == 12
     assert fa.fa_strerror(-99) == "unknown error code"
 
 
@@ -84,8 +85,8 @@ def test_splitkv_argument_errors_come_back_before_any_launch(lib, change, code):
 @pytest.mark.parametrize("decode_kernel", ["stream", "mfma"])
 def test_splitkv_plan(lib, monkeypatch, decode_kernel):
     """Nq = 1 goes to the streaming kernel (one workgroup per (batch, head) and run, no rounding of the grid)
-    unless FA_DECODE=mfma keeps it on the tile kernel; everything else is the tile kernel's either way."""
-    monkeypatch.setenv("FA_DECODE", decode_kernel)
+    unless FA_OPT_DECODE_KERNEL = 1 keeps it on the tile kernel; everything else is the tile kernel's either way."""
+    options.set_decode(decode_kernel)
     stream = decode_kernel == "stream"
     # given nsplit: kept, clamped to the number of 64-key tiles
     p = fa.fa_fwd_splitkv_plan(2, 4, 1, 64 * 100, 128, 1, 0, 7)
@@ -136,16 +137,48 @@ def test_attn_linear_argument_errors_come_back_before_any_launch(lib, change, co
     assert e.value.code == code
 
 
-def test_probe_argument_errors(lib):
+def test_bench_libraries_export_what_their_header_declares_and_the_product_library_does_not(lib):
+    """The measurement aids live in libraries of their own (include/fa_bench.h)."""
     import ctypes
+    from paper_2410_16663_amd import bench_binding as fb, build
+    build.build_bench(force=False)
+    hdr = open(os.path.join(ROOT, "include", "fa_bench.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(fb.GPU_EXPORTS) | set(fb.CPU_EXPORTS)
+    g, c = fb.load_gpu(), fb.load_cpu()
+    assert all(hasattr(g, n) for n in fb.GPU_EXPORTS) and all(hasattr(c, n) for n in fb.CPU_EXPORTS)
+    assert not hasattr(lib, "fa_mfma_probe")
     f = ctypes.c_longlong()
+    assert g.fa_mfma_probe(0, 0, 10, None, ctypes.byref(f), None) == -1
+    assert g.fa_mfma_probe(0, 1, 10, 0x1000, None, None) == -1
+    assert g.fa_mfma_probe(2, 0, 10, 0x1000, ctypes.byref(f), None) == -4
+    assert g.fa_mfma_probe(0, 0, 0, 0x1000, ctypes.byref(f), None) == -2
+    assert g.fa_mfma_probe(0, 2, 10, 0x1000, ctypes.byref(f), None) == -2
+    assert g.fa_mfma_probe(0, 1, 10, 0x1002, ctypes.byref(f), None) == -6
+
+
+def test_options_take_only_their_values_and_return_the_previous_one(lib):
+    assert fa.fa_set_option(fa.FA_OPT_FWD_MODE, fa.FA_MODE_WIDE) == fa.FA_AUTO
+    assert fa.fa_set_option(fa.FA_OPT_FWD_MODE, fa.FA_MODE_SPLIT) == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_SPLIT
+    assert fa.fa_set_option(fa.FA_OPT_FWD_MODE, fa.FA_AUTO) == fa.FA_MODE_SPLIT
+    assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
     L = fa.load()
-    assert L.fa_mfma_probe(0, 0, 10, None, ctypes.byref(f), None) == fa.FA_ERR_NULL
-    assert L.fa_mfma_probe(0, 1, 10, 0x1000, None, None) == fa.FA_ERR_NULL
-    assert L.fa_mfma_probe(2, 0, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_DTYPE
-    assert L.fa_mfma_probe(0, 0, 0, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
-    assert L.fa_mfma_probe(0, 2, 10, 0x1000, ctypes.byref(f), None) == fa.FA_ERR_SHAPE
-    assert L.fa_mfma_probe(0, 1, 10, 0x1002, ctypes.byref(f), None) == fa.FA_ERR_ALIGN
+    for opt, bad in ((fa.FA_OPT_FWD_MODE, 7), (fa.FA_OPT_FWD_MODE, fa.FA_MODE_STREAM), (fa.FA_OPT_DECODE_KERNEL, 2),
+                     (fa.FA_OPT_LINEAR_TILE, 64), (fa.FA_OPT_LINEAR_PANEL, 0), (9, 0), (-1, 0)):
+        assert L.fa_set_option(opt, bad) == fa.FA_ERR_OPTION
+    with pytest.raises(fa.FaError):
+        fa.fa_set_option(fa.FA_OPT_LINEAR_TILE, 100)
+    for opt in range(4):
+        assert L.fa_set_option(opt, fa.FA_AUTO) == fa.FA_AUTO       # the failed calls changed nothing
+
+
+def test_the_library_reads_no_environment_variable(lib, monkeypatch):
+    monkeypatch.setenv("FA_FWD_MODE", "split")
+    monkeypatch.setenv("FA_DECODE", "mfma")
+    assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
+    assert fa.fa_fwd_plan(2, 4, 1, 6400, 128, 1, 0).mode == fa.FA_MODE_STREAM
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
@@ -166,7 +199,7 @@ def golden():
 def test_causal_plan_skips_the_tiles_above_the_diagonal(lib, monkeypatch, mode, T):
     """Square causal problem of T query blocks: block i sees i+1 of the T key blocks, so the
     walked fraction is (T+1)/(2T) -- the paper's "approximately 50%" for long sequences."""
-    monkeypatch.setenv("FA_FWD_MODE", mode)
+    options.set_fwd_mode(mode)
     bm = 128 if mode == "split" else 256
     N = T * bm
     plan = fa.fa_fwd_plan(2, 3, N, N, 128, 1, 1)
@@ -195,7 +228,7 @@ def folded_rows(G, g, Nq):
 def test_plan_matches_brute_force_on_ragged_shapes(lib, monkeypatch):
     import itertools
     for mode, bm in (("split", 128), ("wide", 256), ("fold", 256)):
-        monkeypatch.setenv("FA_FWD_MODE", mode)
+        options.set_fwd_mode(mode)
         for Nq, Nk, causal in itertools.product((1, 100, 257, 640, 2048), (1, 63, 64, 65, 1000, 2048), (0, 1)):
             plan = fa.fa_fwd_plan(1, 1, Nq, Nk, 64, causal, 0)
             G = -(-Nq // bm)
@@ -222,13 +255,13 @@ def test_folded_assignment_balances_the_triangle(lib, monkeypatch):
     assert max(work) - min(work) <= 32 * 32 * 8          # within one block-diagonal of each other
     plain = [sum(i + 1 for i in range(g * 256, g * 256 + 256)) for g in range(G)]
     assert max(plain) > 10 * min(plain)
-    monkeypatch.setenv("FA_FWD_MODE", "fold")
+    options.set_fwd_mode("fold")
     assert fa.fa_fwd_plan(1, 32, Nq, Nq, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD
     assert fa.fa_fwd_plan(1, 32, Nq, Nq, 128, 0, 0).mode == fa.FA_MODE_WIDE     # no triangle to balance
 
 
 def test_mode_heuristic_and_override(lib, monkeypatch):
-    monkeypatch.delenv("FA_FWD_MODE", raising=False)
+    options.set_fwd_mode(None)
     assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD  # 256 wide blocks: one per CU
     assert fa.fa_fwd_plan(1, 32, 2048, 2048, 128, 0, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 4, 4096, 4096, 128, 1, 0).mode == fa.FA_MODE_SPLIT       # 64 wide blocks: too few
@@ -243,10 +276,10 @@ def test_mode_heuristic_and_override(lib, monkeypatch):
     assert fa.fa_fwd_plan(1, 8, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_SPLIT
     assert fa.fa_fwd_plan(1, 16, 8192, 8192, 128, 1, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 0, 0).mode == fa.FA_MODE_WIDE       # not causal: nothing to even out
-    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    options.set_fwd_mode("wide")
     assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).mode == fa.FA_MODE_WIDE
     assert fa.fa_fwd_plan(1, 2, 256, 256, 64, 1, 0).lds_bytes == 4 * 64 * 64 * 2
-    monkeypatch.setenv("FA_FWD_MODE", "split")
+    options.set_fwd_mode("split")
     assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).lds_bytes == 2 * 4 * 64 * 128 * 2
 
 
@@ -270,8 +303,8 @@ def test_build_report_shows_register_only_kernels():
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
     # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
-    # heights; matrix-only probe: 2 dtypes x 2 operand patterns; streaming decode: 2 dtypes x 2 head dims x (plain, masked)
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 4 + 8
+    # heights; streaming decode: 2 dtypes x 2 head dims x (plain, masked)
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 8
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= 256, name

@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 from paper_2410_16663_amd import inputs as I
+import options
 from gpu_util import check_against_oracle, run_attn_linear, run_fa_fwd
 
 pytestmark = pytest.mark.gpu
@@ -38,8 +39,8 @@ def check_y(y, y_ref, label):
 
 @pytest.fixture(params=["128", "256"], autouse=True)
 def tile(request, monkeypatch):
-    """Force each workgroup tile height of the projection kernel in turn (FA_LINEAR_TILE of include/fa.h)."""
-    monkeypatch.setenv("FA_LINEAR_TILE", request.param)
+    """Force each workgroup tile height of the projection kernel in turn (FA_OPT_LINEAR_TILE of include/fa.h)."""
+    options.set_linear_tile(request.param)
     return request.param
 
 
@@ -69,7 +70,7 @@ def test_whole_problem_in_blocks(oracle, shape, rows_per_block, causal, dtype):
 def test_blocks_are_independent_and_touch_only_their_rows(oracle, monkeypatch, mode):
     """Arbitrary blocks, out of order, leaving a gap: the gap's rows of o, lse, y stay as they were.  Every
     decomposition of the attention launch is run on a block whose first row is not row 0."""
-    monkeypatch.setenv("FA_FWD_MODE", mode)
+    options.set_fwd_mode(mode)
     print(f"case attn_linear arbitrary blocks mode={mode}", flush=True)
     rng = np.random.default_rng(601)
     B, H, Nq, Nk, D, N = 2, 2, 1400, 1450, 128, 256
@@ -88,7 +89,7 @@ def test_blocks_are_independent_and_touch_only_their_rows(oracle, monkeypatch, m
 
 def test_tile_order_changes_no_bit(monkeypatch, tile):
     """The order in which the projection's tiles are dealt to the compute units (panels of a few row tiles,
-    FA_LINEAR_PANEL of include/fa.h) decides which workgroup computes a tile, never what it computes: every
+    FA_OPT_LINEAR_PANEL of include/fa.h) decides which workgroup computes a tile, never what it computes: every
     panel height, also ones that do not divide the number of row tiles, gives the same y bit for bit."""
     print(f"case attn_linear tile order tile={tile}", flush=True)
     rng = np.random.default_rng(603)
@@ -96,11 +97,11 @@ def test_tile_order_changes_no_bit(monkeypatch, tile):
     q, k, v, w = make(rng, B, H, Nq, Nk, D, N, I.BF16)
     results = []
     for panel in ("1", "3", "4", "7", "1000"):
-        monkeypatch.setenv("FA_LINEAR_PANEL", panel)
+        options.set_linear_panel(panel)
         o, lse, y = run_attn_linear(q, k, v, w, 0.12, True, I.BF16)
         assert np.isfinite(y).all()
         results.append(y)
-    monkeypatch.delenv("FA_LINEAR_PANEL")
+    options.set_linear_panel(None)
     o, lse, y = run_attn_linear(q, k, v, w, 0.12, True, I.BF16)
     for r in results:
         assert np.array_equal(r, y)
@@ -133,7 +134,7 @@ def test_llama7b_layer_shape_on_sampled_tokens(oracle):
     y_ref = oracle.attention_linear(q, k, v, w, cfg.scale, cfg.causal, cfg.dtype, rows=rows)
     check_y(y[0, rows], y_ref, "C2 projection sample")
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype)
-    check_against_oracle(o, lse, o_ref, lse_ref, cfg.dtype, "C2 in blocks")
+    check_against_oracle(o, lse, o_ref, lse_ref, cfg.dtype, "C2 in blocks", named_config=True)
 
 
 def test_blocks_pipeline_with_a_consumer_on_a_second_stream():

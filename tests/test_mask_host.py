@@ -138,12 +138,9 @@ def test_causal_walk_matches_the_causal_plan(lib):
         walk = fa.fa_mask_tile_walk(-1, 0, 0, Nk, Nq, Nk, R0, R0 + 255)
         assert walk == list(range((R0 + 255) // BN + 1))
     total = sum(len(fa.fa_mask_tile_walk(-1, 0, 0, Nk, Nq, Nk, R0, R0 + 255)) for R0 in range(0, Nq, 256))
-    import os
-    os.environ["FA_FWD_MODE"] = "wide"
-    try:
-        assert total == fa.fa_fwd_plan(1, 1, Nq, Nk, 128, 1, 0).tiles_visited
-    finally:
-        del os.environ["FA_FWD_MODE"]
+    import options
+    options.set_fwd_mode("wide")
+    assert total == fa.fa_fwd_plan(1, 1, Nq, Nk, 128, 1, 0).tiles_visited
 
 
 def test_sliding_window_walk_is_short(lib):
@@ -212,5 +209,11 @@ def test_null_descriptor_and_bad_host_queries(lib):
         fa.fa_mask_tile_walk(-1, 0, -2, 8, 8, 8, 0, 7)
     import ctypes
     m = fa.FaMask(-1, 0, 0, None)
-    i3 = [ctypes.c_int() for _ in range(3)]
-    assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, *[ctypes.byref(x) for x in i3], None) == fa.FA_ERR_NULL
+    tiles, n = (ctypes.c_int * 4)(), ctypes.c_int()
+    assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, tiles, 4, None) == fa.FA_ERR_NULL
+    assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, None, 4, ctypes.byref(n)) == fa.FA_ERR_NULL
+    assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, tiles, -1, ctypes.byref(n)) == fa.FA_ERR_SHAPE
+    # a short array gets the first tiles only; the count is the whole walk's
+    m2 = fa.FaMask(-1, 0, 0, None)
+    assert fa.load().fa_mask_tile_walk(ctypes.byref(m2), 640, 640, 640, 384, 639, tiles, 4, ctypes.byref(n)) == fa.FA_OK
+    assert n.value == 10 and list(tiles) == [0, 1, 2, 3]

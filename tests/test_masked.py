@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 from paper_2410_16663_amd import inputs as I
+import options
 from gpu_util import check_against_oracle, run_fa_decode_masked, run_fa_fwd, run_fa_fwd_masked
 
 pytestmark = pytest.mark.gpu
@@ -67,7 +68,7 @@ def test_long_windows_walked_in_rotated_order(oracle, shape, mask, dtype):
 def test_causal_and_unmasked_descriptors_equal_fa_fwd_bit_for_bit(monkeypatch):
     """(-1, 0) and (-1, -1) walk the same tiles with the same arithmetic as fa_fwd's wide mode."""
     print("case masked vs fa_fwd", flush=True)
-    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    options.set_fwd_mode("wide")
     rng = np.random.default_rng(401)
     for dtype, D in ((I.F16, 64), (I.BF16, 128)):
         q, k, v = (rand_bits(rng, (2, 2, n, D), dtype) for n in (600, 900, 900))
@@ -107,7 +108,8 @@ def test_sliding_window_at_full_size_on_sampled_rows(oracle):
     o, lse = run_fa_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0)
     rows = I.sample_rows(cfg, per_head=16)
     o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0, rows=rows)
-    check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, "SWA sample")
+    check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, "SWA sample",
+                         named_config=True)
 
 
 DECODE_MASKS = [
@@ -124,8 +126,8 @@ DECODE_MASKS = [
 def test_single_query_under_descriptor_masks(oracle, monkeypatch, mask, dtype, kernel):
     """A decoding step (Nq = 1) over caches of different lengths, with a sliding window and / or a prefix that
     stays visible: the streaming kernel walks the prefix and the window as two runs of consecutive keys (one if
-    they touch, none if the cache is empty); FA_DECODE=mfma keeps the tile kernel.  Both against the oracle."""
-    monkeypatch.setenv("FA_DECODE", kernel)
+    they touch, none if the cache is empty); FA_OPT_DECODE_KERNEL = 1 keeps the tile kernel.  Both against the oracle."""
+    options.set_decode(kernel)
     left, right, prefix, frac = mask
     B, H, Nk = 3, 2, 3001
     for D in (64, 128):

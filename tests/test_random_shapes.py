@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 from paper_2410_16663_amd import inputs as I
+import options
 from gpu_util import (check_against_oracle, run_attn_linear, run_fa_fwd, run_fa_fwd_masked,
                       run_fa_fwd_splitkv)
 
@@ -46,7 +47,7 @@ def test_fa_fwd_random(oracle, monkeypatch, case):
     causal = bool(rng.integers(0, 2))
     mode = str(rng.choice(["auto", "split", "wide", "fold"]))
     if mode != "auto":
-        monkeypatch.setenv("FA_FWD_MODE", mode)
+        options.set_fwd_mode(mode)
     label = f"fa_fwd case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} scale={scale:.3f} causal={causal} mode={mode}"
     print("case " + label, flush=True)
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
@@ -63,7 +64,7 @@ def test_fa_fwd_splitkv_random(oracle, monkeypatch, case):
     causal = bool(rng.integers(0, 2))
     nsplit = int(rng.choice([0, 1, 2, 3, 5, 8, 13, 40, 1024]))
     kern = str(rng.choice(["stream", "mfma"]))
-    monkeypatch.setenv("FA_DECODE", kern)
+    options.set_decode(kern)
     label = (f"splitkv case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} scale={scale:.3f} causal={causal} "
              f"nsplit={nsplit} decode={kern}")
     print("case " + label, flush=True)
@@ -102,7 +103,7 @@ def test_fa_attn_linear_random(oracle, monkeypatch, case):
     causal = bool(rng.integers(0, 2))
     N = int(rng.choice([256, 512, 768]))
     rpb = int(rng.choice([0, 64, 100, 128, 257]))
-    monkeypatch.setenv("FA_LINEAR_TILE", str(rng.choice(["128", "256"])))
+    options.set_linear_tile(str(rng.choice(["128", "256"])))
     label = (f"attn_linear case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} N={N} dt={dtype} scale={scale:.3f} "
              f"causal={causal} rows_per_block={rpb}")
     print("case " + label, flush=True)
@@ -151,7 +152,7 @@ def test_fa_fwd_random_medium(oracle, monkeypatch, case):
     causal = rng.random() < 0.7
     mode = str(rng.choice(["auto", "split", "wide", "fold"]))
     if mode != "auto":
-        monkeypatch.setenv("FA_FWD_MODE", mode)
+        options.set_fwd_mode(mode)
     label = f"fa_fwd medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} causal={causal} mode={mode}"
     print("case " + label, flush=True)
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
@@ -191,7 +192,7 @@ def test_fa_fwd_splitkv_random_medium(oracle, monkeypatch, case):
     causal = bool(rng.integers(0, 2))
     nsplit = int(rng.choice([0, 0, 2, 7, 31, 200]))
     kern = str(rng.choice(["stream", "mfma"]))
-    monkeypatch.setenv("FA_DECODE", kern)
+    options.set_decode(kern)
     label = (f"splitkv medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} causal={causal} "
              f"nsplit={nsplit} decode={kern}")
     print("case " + label, flush=True)
@@ -211,7 +212,7 @@ def test_fa_attn_linear_random_medium(oracle, monkeypatch, case):
     causal = bool(rng.integers(0, 2))
     N = int(rng.choice([256, 1024]))
     rpb = int(rng.choice([0, 256, 700, 1024]))
-    monkeypatch.setenv("FA_LINEAR_TILE", str(rng.choice(["128", "256"])))
+    options.set_linear_tile(str(rng.choice(["128", "256"])))
     label = (f"attn_linear medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} N={N} dt={dtype} causal={causal} "
              f"rows_per_block={rpb}")
     print("case " + label, flush=True)

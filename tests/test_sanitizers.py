@@ -14,7 +14,8 @@ def test_host_c_code_is_clean_under_asan_and_ubsan(tmp_path, force_scalar):
     exe = str(tmp_path / "driver_host")
     cmd = ["gcc", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
            os.path.join(ROOT, "tests", "sanitize", "driver_host.c"), os.path.join(ROOT, "oracle", "fa_oracle.c"),
-           os.path.join(ROOT, "paper_2410_16663_amd", "csrc", "fa_cpu.c"), "-o", exe, "-lm"]
+           os.path.join(ROOT, "paper_2410_16663_amd", "csrc", "fa_cpu.c"),
+           os.path.join(ROOT, "paper_2410_16663_amd", "csrc", "fa_bench_cpu.c"), "-o", exe, "-lm"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
     env = dict(os.environ)
@@ -49,6 +50,7 @@ for B, H, Nq, Nk, D, causal in itertools.product((1, 7, 70000), (1, 33, 70000), 
     lib.fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, 1, 1024, ctypes.byref(s))
     n += 1
 i3 = [ctypes.c_int() for _ in range(4)]
+tiles = (ctypes.c_int * 64)()
 for l, r, pfx in itertools.product((-1, 0, 63, 5000, big), (-1, 0, 100, big), (0, 1, 700, big)):
     for Nq, Nk in ((1, 1), (300, 300), (130, 70000), (70000, 130), (2**29 - 100, 2**29), (2**30, 64)):
         m = Mask(l, r, pfx, None)
@@ -58,7 +60,7 @@ for l, r, pfx in itertools.product((-1, 0, 63, 5000, big), (-1, 0, 100, big), (0
                 for k0 in (0, (Nk - 1) // 64 * 64):
                     lib.fa_mask_tile_class(ctypes.byref(m), klen, Nq, Nk, r0, r1, k0)
                 R1 = min(r0 + 255, Nq - 1)
-                lib.fa_mask_tile_walk(ctypes.byref(m), klen, Nq, Nk, r0, R1, *[ctypes.byref(x) for x in i3])
+                lib.fa_mask_tile_walk(ctypes.byref(m), klen, Nq, Nk, r0, R1, tiles, 64, ctypes.byref(i3[2]))
                 lib.fa_mask_interior_run(ctypes.byref(m), klen, Nq, Nk, r0, R1, r0, r1, ctypes.byref(i3[0]), ctypes.byref(i3[1]))
                 n += 1
 # argument errors of the launching entry points (nothing is launched)

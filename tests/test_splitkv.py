@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 from paper_2410_16663_amd import inputs as I
+import options
 from gpu_util import check_against_oracle, run_fa_fwd, run_fa_fwd_splitkv
 
 pytestmark = pytest.mark.gpu
@@ -30,9 +31,9 @@ CHUNK_SHAPES = [
 
 @pytest.fixture(params=["stream", "mfma"])
 def decode_kernel(request, monkeypatch):
-    """Both kernels a single-query problem can take: the register-streaming one and (FA_DECODE=mfma of
+    """Both kernels a single-query problem can take: the register-streaming one and (FA_OPT_DECODE_KERNEL = 1 of
     include/fa.h) the tile kernel every other shape runs."""
-    monkeypatch.setenv("FA_DECODE", request.param)
+    options.set_decode(request.param)
     return request.param
 
 
@@ -120,11 +121,8 @@ def test_streaming_and_tile_kernels_agree():
         q, k, v = (rand_bits(rng, (2, 3, n, D), dtype) for n in (1, 9000, 9000))
         res = {}
         for kern in ("stream", "mfma"):
-            os.environ["FA_DECODE"] = kern
-            try:
-                res[kern] = run_fa_fwd_splitkv(q, k, v, 0.1, True, dtype, 0)
-            finally:
-                del os.environ["FA_DECODE"]
+            options.set_decode(kern)
+            res[kern] = run_fa_fwd_splitkv(q, k, v, 0.1, True, dtype, 0)
         (o0, lse0, p0), (o1, lse1, p1) = res["stream"], res["mfma"]
         assert p0.streaming == 1 and p1.streaming == 0
         d = np.abs(I.bits_to_f64(o0, dtype) - I.bits_to_f64(o1, dtype))
@@ -135,7 +133,7 @@ def test_matches_fa_fwd_and_ignores_workspace_contents(monkeypatch):
     """Same inputs through both entry points: equal up to fp32 rounding order; a larger, NaN-filled
     workspace changes nothing; one run (nsplit = 1) walks the tiles exactly as fa_fwd's wide mode does."""
     print("case splitkv vs fa_fwd", flush=True)
-    monkeypatch.setenv("FA_FWD_MODE", "wide")
+    options.set_fwd_mode("wide")
     rng = np.random.default_rng(181)
     for dtype in (I.F16, I.BF16):
         q, k, v = (rand_bits(rng, (2, 2, n, 128), dtype) for n in (70, 3000, 3000))
@@ -160,7 +158,8 @@ def test_decode_at_cache_size_on_sampled_heads(oracle):
     for b, h in ((0, 0), (1, 17), (1, 31), (0, 8)):
         o_ref, lse_ref = oracle.attention_fwd(q[b:b + 1, h:h + 1], k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1],
                                               cfg.scale, cfg.causal, cfg.dtype)
-        check_against_oracle(o[b:b + 1, h:h + 1], lse[b:b + 1, h:h + 1], o_ref, lse_ref, cfg.dtype, f"head {b},{h}")
+        check_against_oracle(o[b:b + 1, h:h + 1], lse[b:b + 1, h:h + 1], o_ref, lse_ref, cfg.dtype, f"DEC head {b},{h}",
+                             named_config=True)
 
 
 @pytest.mark.parametrize("kernel", ["stream", "mfma"])
@@ -169,7 +168,7 @@ def test_cache_of_more_than_2_to_31_elements(oracle, monkeypatch, kernel):
     offsets.  Inputs drawn on the GPU; the first, a middle and the very last head are checked against the oracle."""
     import torch
     from paper_2410_16663_amd import binding as fa
-    monkeypatch.setenv("FA_DECODE", kernel)
+    options.set_decode(kernel)
     B, H, Nk, D, dtype = 64, 32, 8192, 128, I.F16
     print(f"case splitkv large cache B={B} H={H} Nk={Nk} D={D} kernel={kernel}", flush=True)
     dev = torch.device("cuda:0")
