@@ -213,7 +213,10 @@ def test_single_query_goes_through_the_streaming_kernel(oracle, monkeypatch, sha
     o_t, lse_t = run_fa_fwd(q, k, v, scale, True, dtype)
     check_against_oracle(o_t, lse_t, o_ref, lse_ref, dtype, f"{shape} tile")
     d = np.abs(I.bits_to_f64(o_c, dtype) - I.bits_to_f64(o_t, dtype))
-    assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2) and np.abs(lse_c - lse_t).max() <= 1e-5
+    # lse: the tile kernels' fp16 row sum adds up the probabilities as rounded to fp16 (2^-11 relative per term at worst,
+    # far less once a few terms average out); their bf16 row sum is unrounded, like the streaming kernel's
+    assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2)
+    assert np.abs(lse_c - lse_t).max() <= (2.5e-4 if dtype == I.F16 else 1e-5)
 
 
 def test_tensors_of_more_than_2_to_31_elements(oracle):

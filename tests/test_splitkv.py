@@ -126,7 +126,9 @@ def test_streaming_and_tile_kernels_agree():
         (o0, lse0, p0), (o1, lse1, p1) = res["stream"], res["mfma"]
         assert p0.streaming == 1 and p1.streaming == 0
         d = np.abs(I.bits_to_f64(o0, dtype) - I.bits_to_f64(o1, dtype))
-        assert d.max() <= (1e-3 if dtype == I.F16 else 8e-3) and np.abs(lse0 - lse1).max() <= 1e-5
+        assert d.max() <= (1e-3 if dtype == I.F16 else 8e-3)
+        # the tile kernels' fp16 row sum adds up the probabilities as rounded to fp16; bf16's and the streaming kernel's do not
+        assert np.abs(lse0 - lse1).max() <= (2.5e-4 if dtype == I.F16 else 1e-5)
 
 
 def test_matches_fa_fwd_and_ignores_workspace_contents(monkeypatch):
@@ -144,7 +146,8 @@ def test_matches_fa_fwd_and_ignores_workspace_contents(monkeypatch):
         o3, lse3, _ = run_fa_fwd_splitkv(q, k, v, 0.09, True, dtype, 6, extra_workspace=4096)
         assert np.array_equal(o2, o3) and np.array_equal(lse2, lse3)
         d = np.abs(I.bits_to_f64(o0, dtype) - I.bits_to_f64(o2, dtype))
-        assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2) and np.abs(lse0 - lse2).max() <= 1e-5
+        assert d.max() <= (2e-3 if dtype == I.F16 else 1.6e-2)
+        assert np.abs(lse0 - lse2).max() <= (2.5e-4 if dtype == I.F16 else 1e-5)
 
 
 def test_decode_at_cache_size_on_sampled_heads(oracle):
