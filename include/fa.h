@@ -140,6 +140,26 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
                    int B, int H, int Nq, int Nk, int D, float scale, int causal, int dtype,
                    int nsplit, void *workspace, long long workspace_bytes, void *stream);
 
+/*
+ * fa_fwd_splitkv_static -- fa_fwd_splitkv for callers that cannot allocate or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for
+ * bit) and error codes as fa_fwd_splitkv without `workspace` / `workspace_bytes`: the partial results go to a
+ * 64 MiB array that is part of the library's device code (each GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates and frees nothing, on the host or on the device.
+ *
+ *   limit   : fa_fwd_splitkv_plan(...).workspace_bytes = nsplit * B * H * Nq * (D + 2) * 4 must not exceed
+ *             64 MiB (67108864 bytes), else FA_ERR_WORKSPACE and nothing is launched; with a single run
+ *             (chosen or asked for) no workspace is needed and the limit does not apply
+ *   sharing : every call on one GPU uses that GPU's one array.  Nothing in it needs clearing (every partial
+ *             result is written before it is read), but calls that may overlap on one GPU -- different
+ *             streams, different threads -- race on it: keep them ordered (one stream, or events).
+ *   first call on a device: looks the array's device address up (hipGetSymbolAddress, once per device, the
+ *             device being current); make that call outside of a graph capture.
+ */
+int fa_fwd_splitkv_static(const void *q, const void *k, const void *v, void *o, float *lse,
+                          int B, int H, int Nq, int Nk, int D, float scale, int causal, int dtype,
+                          int nsplit, void *stream);
+
 typedef struct fa_splitkv_plan {
     int nsplit;                 /* runs actually used */
     int grid_x, grid_y;         /* first kernel: work items (tile kernel: rounded up to a multiple of 8) x runs */

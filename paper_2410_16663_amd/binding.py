@@ -40,7 +40,7 @@ FA_MODE_WIDE_FOLD = 2
 FA_MODE_STREAM = 3
 
 # every symbol include/fa.h declares
-EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
+EXPORTS = ("fa_fwd", "fa_fwd_plan", "fa_fwd_splitkv", "fa_fwd_splitkv_static", "fa_fwd_splitkv_plan", "fa_fwd_masked", "fa_attn_linear_block",
            "fa_attn_linear", "fa_mask_tile_class",
            "fa_mask_tile_walk", "fa_mask_interior_run", "fa_set_option", "fa_strerror", "fa_version", "fa_last_hip_error",
            "fa_decode_masked")
@@ -116,6 +116,9 @@ def load() -> ctypes.CDLL:
         lib.fa_fwd_splitkv.restype = ctypes.c_int
         lib.fa_fwd_splitkv.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
             ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_longlong, vp]
+        lib.fa_fwd_splitkv_static.restype = ctypes.c_int
+        lib.fa_fwd_splitkv_static.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [
+            ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
         lib.fa_fwd_splitkv_plan.restype = ctypes.c_int
         lib.fa_fwd_splitkv_plan.argtypes = [ctypes.c_int] * 8 + [ctypes.POINTER(FaSplitKvPlan)]
         lib.fa_attn_linear_block.restype = ctypes.c_int
@@ -192,6 +195,20 @@ def fa_fwd_splitkv(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nspli
     """fa_fwd_splitkv of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
     rc = fa_fwd_splitkv_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, workspace,
                             workspace_bytes, stream)
+    if rc != FA_OK:
+        raise FaError(rc)
+
+
+def fa_fwd_splitkv_static_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, stream=0) -> int:
+    """Call fa_fwd_splitkv_static and return its status code unchanged."""
+    return load().fa_fwd_splitkv_static(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nq),
+                                        int(Nk), int(D), float(scale), int(causal), int(dtype), int(nsplit),
+                                        _addr(stream))
+
+
+def fa_fwd_splitkv_static(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, stream=0) -> None:
+    """fa_fwd_splitkv_static of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
+    rc = fa_fwd_splitkv_static_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, stream)
     if rc != FA_OK:
         raise FaError(rc)
 

@@ -46,10 +46,17 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
 #include "../../include/fa.h"
+
+// Workspace of fa_fwd_splitkv_static: the split-KV partial results of callers that cannot pass a workspace of their
+// own.  Every GPU the library's code object is loaded on holds its own copy at its own address, until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+#define FA_STATIC_WORKSPACE_BYTES (64ll << 20)
+static __device__ __align__(256) unsigned char scratch[FA_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -467,6 +474,46 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
     return FA_OK;
 }
 
+int fa_fwd_splitkv_static(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq,
+                          int Nk, int D, float scale, int causal, int dtype, int nsplit, void *stream) {
+    // every argument check first (no HIP call before them), the size limit among them
+    if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
+    fa_splitkv_plan_t pl;
+    const int rc = fa_fwd_splitkv_plan(B, H, Nq, Nk, D, causal, dtype, nsplit, &pl);
+    if (rc != FA_OK) return rc;
+    if (!isfinite(scale)) return FA_ERR_SCALE;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
+    if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
+    if (pl.nsplit == 1) return fa_fwd(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, stream);   // nothing to merge
+    if (pl.workspace_bytes > FA_STATIC_WORKSPACE_BYTES) return FA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    {
+        // the array's device address on the current GPU, asked for once per device and kept
+        constexpr int MAX_DEVICES = 64;
+        static std::mutex lock;
+        static void *address[MAX_DEVICES] = {};
+        int dev = -1;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess && (dev < 0 || dev >= MAX_DEVICES)) e = hipErrorInvalidDevice;
+        if (e == hipSuccess) {
+            std::lock_guard<std::mutex> guard(lock);
+            if (!address[dev]) {
+                void *ptr = nullptr;
+                e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+                if (e == hipSuccess && !ptr) e = hipErrorInvalidSymbol;
+                if (e == hipSuccess) address[dev] = ptr;
+            }
+            ws = address[dev];
+        }
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+    }
+    return fa_fwd_splitkv(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, nsplit, ws, FA_STATIC_WORKSPACE_BYTES,
+                          stream);
+}
+
 int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
                   int D, float scale, const fa_mask_t *mask, int dtype, void *stream) {
     if (!q || !k || !v || !o || !lse || !mask) return FA_ERR_NULL;
@@ -703,7 +750,9 @@ const char *fa_strerror(int code) {
         case FA_ERR_SCALE: return "scale must be finite";
         case FA_ERR_ALIGN: return "q, k, v, o must be 16-byte aligned and lse 4-byte aligned";
         case FA_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
-        case FA_ERR_WORKSPACE: return "workspace is NULL or smaller than fa_fwd_splitkv_plan reports";
+        case FA_ERR_WORKSPACE:
+            return "workspace is NULL or smaller than fa_fwd_splitkv_plan reports (fa_fwd_splitkv_static: the problem needs "
+                   "more than the library's 64 MiB)";
         case FA_ERR_NSPLIT: return "nsplit exceeds 1024";
         case FA_ERR_MASK: return "mask descriptor: prefix must be >= 0 and a key count within 0..Nk";
         case FA_ERR_OPTION: return "fa_set_option: unknown option, or a value it does not take";
