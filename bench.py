@@ -486,6 +486,8 @@ def main():
                     help="with --projection-only: also time the two-stream pipeline with the exchange stand-in")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
+    ap.add_argument("--fwd-mode", default=None, choices=["split", "wide", "fold"],
+                    help="force fa_fwd's work decomposition (fa_set_option; for profiling and tuning runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle (baseline and parity)")
     ap.add_argument("--gpu-inputs", action="store_true",
@@ -516,6 +518,9 @@ def main():
     fa.load()   # fails loudly if libfa.so is missing; there is no fallback
     torch.cuda.set_device(0)
 
+    if args.fwd_mode:
+        fa.fa_set_option(fa.FA_OPT_FWD_MODE, {"split": fa.FA_MODE_SPLIT, "wide": fa.FA_MODE_WIDE,
+                                              "fold": fa.FA_MODE_WIDE_FOLD}[args.fwd_mode])
     cfg = I.CONFIGS[args.workload]
     if args.copy_calibration > 0:
         n = args.copy_calibration * (1 << 20) // 4

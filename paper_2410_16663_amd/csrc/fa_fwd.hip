@@ -148,7 +148,7 @@ bool use_streaming_decode(int Nq) { return Nq == 1 && option(FA_OPT_DECODE_KERNE
 //    FA_MODE_SPLIT, whose shorter chains matter more than its extra K/V traffic;
 //  * otherwise FA_MODE_WIDE: with many rounds the heavy-first dynamic dispatch evens out the triangle.
 // fa_set_option(FA_OPT_FWD_MODE, ...) overrides.
-int choose_mode(int B, int H, int Nq, int causal) {
+int choose_mode(int B, int H, int Nq, int D, int causal) {
     const int forced = option(FA_OPT_FWD_MODE);
     if (forced == FA_MODE_SPLIT || forced == FA_MODE_WIDE) return forced;
     if (forced == FA_MODE_WIDE_FOLD) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
@@ -337,7 +337,7 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
         plan->lds_bytes = DECODE_WAVES * (512 / D) * (D + 2) * 4;     // one partial state per lane group
         return FA_OK;
     }
-    const int mode = choose_mode(B, H, Nq, causal);
+    const int mode = choose_mode(B, H, Nq, D, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
@@ -364,7 +364,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
     if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
 
-    const int mode = use_streaming_decode(Nq) ? FA_MODE_STREAM : choose_mode(B, H, Nq, causal);
+    const int mode = use_streaming_decode(Nq) ? FA_MODE_STREAM : choose_mode(B, H, Nq, D, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;   // query rows per workgroup
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
@@ -622,7 +622,7 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
     // 1. attention of the block's rows, every head: a launch over row_count rows whose diagonal is shifted
     //    by row_first; q, o, lse keep the full tensors' head pitch
     {
-        const int mode = choose_mode(B, H, row_count, causal);
+        const int mode = choose_mode(B, H, row_count, D, causal);
         const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
         const long long nqt = ((long long)row_count + BM - 1) / BM;
         const long long nwork = (long long)B * H * nqt;
