@@ -184,10 +184,10 @@ def decode_entry(I, torch, fa, steps, warmup):
                          "bytes_per_call": kv_bytes}}
 
 
-def sliding_entry(I, torch, fa, steps, warmup):
+def sliding_entry(I, torch, fa, steps, warmup, c=None):
     """A causal sliding window through the descriptor-mask entry point, priced against the MFMA peak with the
     exact number of attending (query, key) pairs: 4*D flop each."""
-    c = I.SLIDING
+    c = c or I.SLIDING
     tq, tk, tv = device_inputs_on_gpu(c, torch)
     dev = tq.device
     to = torch.empty((c.B, c.H, c.Nq, c.D), dtype=torch.int16, device=dev)
@@ -214,8 +214,30 @@ def sliding_entry(I, torch, fa, steps, warmup):
             "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
             "flop_convention": "4*D per attending (query, key) pair, counted exactly",
             "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("masked_SWA"),
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("masked_" + c.name),
                          "kernel": "fa_fwd_kernel (wide, descriptor mask)", "flops_per_launch": c.flops()}}
+
+
+def chunked_entry(I, torch, fa, steps, warmup):
+    """Chunked prefill (a block of new tokens against a long cache) through the split-KV entry point, priced
+    against the MFMA peak with the exact number of attending pairs (the chunk's own triangle is missing from the
+    rectangle)."""
+    c = I.CHUNKED
+    tensors = device_inputs_on_gpu(c, torch)
+    ms, plan = time_decode(c, tensors, steps, warmup, torch, fa)
+    fl = 4.0 * c.D * c.visible_pairs()
+    tf = fl / (ms * 1e-3) / 1e12
+    kv_bytes = 2.0 * c.B * c.H * c.Nk * c.D * 2
+    return {"workload": c.describe(), "entry_point": "fa_fwd_splitkv", "nsplit": plan.nsplit,
+            "grid": [plan.grid_x, plan.grid_y], "ms_per_call": round(ms, 5), "steps": steps,
+            "inputs": "N(0,1) drawn on the GPU (torch generator, same seeds)",
+            "flop_convention": "4*D per attending (query, key) pair, counted exactly",
+            "kv_gb_per_s": round(kv_bytes / (ms * 1e-3) / 1e9, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("splitkv_CHUNK"),
+                         "kernel": "fa_fwd_kernel (wide, split-KV) + fa_combine_kernel", "flops_per_call": fl,
+                         "note": "K and V are read once (512 MiB): at this arithmetic intensity (about 500 flop per "
+                                 "byte) the HBM roofline allows 4 PFLOP/s, so the matrix peak is the bound"}}
 
 
 def projection_entry(I, torch, fa, steps, warmup, overlap_demo=True):
@@ -484,6 +506,10 @@ def main():
                     help="time only the attention + output projection workload (for profiling runs)")
     ap.add_argument("--overlap-demo", action="store_true",
                     help="with --projection-only: also time the two-stream pipeline with the exchange stand-in")
+    ap.add_argument("--chunked-only", action="store_true",
+                    help="time only the chunked-prefill workload through fa_fwd_splitkv (for profiling runs)")
+    ap.add_argument("--sliding64-only", action="store_true",
+                    help="time only the sliding-window workload at head dimension 64 (for profiling runs)")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--fwd-mode", default=None, choices=["split", "wide", "fold"],
@@ -500,7 +526,7 @@ def main():
         args.steps = {"C1": 20000, "C2": 20000, "C3": 200, "C4": 600, "C5": 20}.get(args.workload, 50)
         if args.decode_only:
             args.steps = 2000
-        if args.sliding_only or args.projection_only:
+        if args.sliding_only or args.projection_only or args.sliding64_only or args.chunked_only:
             args.steps = 200
     if args.warmup is None:
         args.warmup = max(1, args.steps // 4)
@@ -532,6 +558,12 @@ def main():
         del src, dst
     if args.sliding_only:
         print(json.dumps({"sliding": sliding_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
+        return
+    if args.sliding64_only:
+        print(json.dumps({"sliding64": sliding_entry(I, torch, fa, args.steps, args.warmup, I.SLIDING64)}), flush=True)
+        return
+    if args.chunked_only:
+        print(json.dumps({"chunked": chunked_entry(I, torch, fa, args.steps, args.warmup)}), flush=True)
         return
     if args.projection_only:
         print(json.dumps({"projection": projection_entry(I, torch, fa, args.steps, args.warmup, args.overlap_demo)}),
@@ -612,6 +644,10 @@ def main():
         extra["DEC"] = decode_entry(I, torch, fa, 500, 50)
         torch.cuda.empty_cache()
         extra["SWA"] = sliding_entry(I, torch, fa, 60, 6)
+        torch.cuda.empty_cache()
+        extra["SWA64"] = sliding_entry(I, torch, fa, 60, 6, I.SLIDING64)
+        torch.cuda.empty_cache()
+        extra["CHUNK"] = chunked_entry(I, torch, fa, 300, 30)
         torch.cuda.empty_cache()
         extra["LIN"] = projection_entry(I, torch, fa, 100, 10)
         extra["CPU_DEC"] = cpu_decode_entry(I, np)

@@ -105,6 +105,16 @@ DECODE = Config("DEC", 6, 2, 32, 1, 32768, 128, BF16, True)
 SLIDING = Config("SWA", 7, 2, 32, 16384, 16384, 128, BF16, True, 1.0, 4096)
 
 
+# The same window at head dimension 64 (64 heads of 64 channels: the same hidden size), so that the descriptor-mask
+# kernel is measured at both head dimensions.
+SLIDING64 = Config("SWA64", 9, 2, 64, 16384, 16384, 64, BF16, True, 1.0, 4096)
+
+# Chunked prefill: a chunk of 512 new tokens attends to a cache of 32768 tokens that ends with the chunk itself
+# (bottom-right-aligned causal mask), one sequence at the same head layout.  512 rows are two query blocks per head,
+# far too few workgroups to fill the chip, so this is the split-KV entry point's other shape (the first being the
+# single-query decoding step).  Not one of the five benchmark configurations.
+CHUNKED = Config("CHUNK", 10, 1, 32, 512, 32768, 128, BF16, True)
+
 # Attention followed by the output projection, block of rows by block of rows (section 4.2): one sequence of
 # 8192 tokens at the same head layout, a 4096 x 4096 projection matrix drawn as N(0,1)/sqrt(4096), blocks of 2048
 # rows.  Not one of the five benchmark configurations.

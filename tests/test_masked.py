@@ -100,15 +100,16 @@ def test_unusual_scales(oracle, scale):
     check_against_oracle(o, lse, o_ref, lse_ref, I.BF16, f"scale={scale}")
 
 
-def test_sliding_window_at_full_size_on_sampled_rows(oracle):
-    """The windowed workload bench.py times (inputs.SLIDING, same seeded tensors): a stratified sample of rows."""
-    cfg = I.SLIDING
+@pytest.mark.parametrize("cfg", [I.SLIDING, I.SLIDING64], ids=["SWA", "SWA64"])
+def test_sliding_window_at_full_size_on_sampled_rows(oracle, cfg):
+    """The windowed workloads bench.py times (inputs.SLIDING / SLIDING64, same seeded tensors): a stratified sample
+    of rows."""
     print("case masked " + cfg.describe(), flush=True)
     q, k, v = I.make_qkv(cfg)
     o, lse = run_fa_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0)
     rows = I.sample_rows(cfg, per_head=16)
     o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, cfg.scale, cfg.dtype, cfg.window - 1, 0, rows=rows)
-    check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, "SWA sample",
+    check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype, cfg.name + " sample",
                          named_config=True)
 
 

@@ -165,6 +165,23 @@ def test_decode_at_cache_size_on_sampled_heads(oracle):
                              named_config=True)
 
 
+def test_chunked_prefill_at_full_size_on_sampled_rows(oracle):
+    """The chunked-prefill workload bench.py times (inputs.CHUNKED, same seeded tensors, library-chosen nsplit): 512
+    new tokens per head against 32768 keys, bottom-right-aligned causal mask; a stratified sample of rows (16 per head,
+    the first and the last row of the chunk among them) is checked."""
+    cfg = I.CHUNKED
+    print("case splitkv " + cfg.describe(), flush=True)
+    q, k, v = I.make_qkv(cfg)
+    o, lse, plan = run_fa_fwd_splitkv(q, k, v, cfg.scale, cfg.causal, cfg.dtype, 0)
+    assert plan.streaming == 0 and plan.nsplit > 1 and plan.grid_x * plan.grid_y >= 256
+    rows = I.sample_rows(cfg, per_head=16, stratum=32)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, cfg.scale, cfg.causal, cfg.dtype, rows=rows)
+    stats = check_against_oracle(o.reshape(-1, cfg.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, cfg.dtype,
+                                 "CHUNK sample", named_config=True)
+    print("CHUNK", stats, flush=True)
+    assert np.isfinite(lse).all()
+
+
 @pytest.mark.parametrize("kernel", ["stream", "mfma"])
 def test_cache_of_more_than_2_to_31_elements(oracle, monkeypatch, kernel):
     """B = 64, H = 32, Nk = 8192, D = 128: K and V hold 2^31 elements each, so the last heads sit past 32-bit
