@@ -65,9 +65,13 @@ int fa_coop_plan_fp16(double m_gpu, int n, int L, long long H1, long long H2, lo
 int fa_cpu_decode(const void *q, const void *k, const void *v, void *o, float *lse,
                   int B, int H, int Nk, int D, float scale, int dtype, int nthreads);
 
-/* 1 if fa_cpu_decode runs its AVX-512 path on this machine, else 0 (the environment variable
-   FA_CPU_FORCE_SCALAR=1 turns the AVX-512 path off, for tests) */
+/* 1 if fa_cpu_decode runs its AVX-512 path on this machine, else 0 */
 int fa_cpu_has_avx512(void);
+
+/* Test hook: on != 0 makes fa_cpu_decode run its plain C loops whatever the CPU has, 0 restores the choice at
+   run time.  Process-wide, read once per fa_cpu_decode call; returns the previous setting.  The library reads no
+   environment variable. */
+int fa_cpu_set_scalar(int on);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ FA_CPU_ERR_SCALE = -5
 FA_CPU_ERR_NOMEM = -8
 
 # every symbol include/fa_cpu.h declares
-EXPORTS = ("fa_coop_plan_bytes", "fa_coop_plan_fp16", "fa_cpu_decode", "fa_cpu_has_avx512")
+EXPORTS = ("fa_coop_plan_bytes", "fa_coop_plan_fp16", "fa_cpu_decode", "fa_cpu_has_avx512", "fa_cpu_set_scalar")
 
 _lib = None
 
@@ -49,6 +49,8 @@ def load() -> ctypes.CDLL:
                                                                                   ctypes.c_int]
         lib.fa_cpu_has_avx512.restype = ctypes.c_int
         lib.fa_cpu_has_avx512.argtypes = []
+        lib.fa_cpu_set_scalar.restype = ctypes.c_int
+        lib.fa_cpu_set_scalar.argtypes = [ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -98,3 +100,7 @@ def fa_cpu_decode(q, k, v, o, lse, B, H, Nk, D, scale, dtype, nthreads=0) -> Non
 
 def fa_cpu_has_avx512() -> bool:
     return bool(load().fa_cpu_has_avx512())
+
+
+def fa_cpu_set_scalar(on: bool) -> bool:
+    return bool(load().fa_cpu_set_scalar(int(bool(on))))

@@ -10,6 +10,7 @@
  * hardware fp16 conversion, a short polynomial for exp) chosen at run time when the CPU has
  * it, and plain C.
  */
+#include <stdatomic.h>
 #include <immintrin.h>
 #include <math.h>
 #include <stdint.h>
@@ -227,9 +228,14 @@ AVX512 static void run_avx512(const float *qf, const uint16_t *k, const uint16_t
     *l_out = l;
 }
 
+static atomic_int g_scalar_only;                          /* for tests: run the plain C loops */
+
+int fa_cpu_set_scalar(int on) {
+    return atomic_exchange(&g_scalar_only, on != 0);
+}
+
 int fa_cpu_has_avx512(void) {
-    const char *env = getenv("FA_CPU_FORCE_SCALAR");      /* for tests: run the plain C loops */
-    if (env && env[0] == '1') return 0;
+    if (atomic_load(&g_scalar_only)) return 0;
     __builtin_cpu_init();
     return __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") &&
            __builtin_cpu_supports("avx512dq") && __builtin_cpu_supports("avx512vl");

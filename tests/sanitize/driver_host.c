@@ -34,7 +34,9 @@ static uint16_t *rand_buf(size_t n) {
 }
 #define CHECK(x) do { int rc_ = (x); if (rc_ != 0) { fprintf(stderr, "%s -> %d\n", #x, rc_); return 1; } } while (0)
 
-int main(void) {
+int main(int argc, char **argv) {
+    const int scalar_only = argc > 1 && argv[1][0] == '1';   /* "1": the plain C loops, else what the CPU has */
+    fa_cpu_set_scalar(scalar_only);
     for (int dtype = 0; dtype < 2; ++dtype)
         for (int causal = 0; causal < 2; ++causal) {
             const int B = 2, H = 3, Nq = 37, Nk = 53, D = 16, N = 5;
@@ -52,7 +54,7 @@ int main(void) {
             CHECK(fa_oracle_attn_linear(q, k, v, w, y, B, H, Nq, Nk, D, N, 0.25, causal, dtype, NULL, 0, 2));
             /* Nq > Nk causal: rows without keys */
             CHECK(fa_oracle_fwd(q, k, v, o, lse, B, H, Nq, 20, D, 0.25, 1, dtype, NULL, 0, 2));
-            /* host decoding attention: one query per head, several runs of keys, both code paths via the environment */
+            /* host decoding attention: one query per head, several runs of keys, the code path chosen by the first argument */
             uint16_t *q1 = rand_buf((size_t)B * H * 64), *k1 = rand_buf((size_t)B * H * 1000 * 64), *v1 = rand_buf((size_t)B * H * 1000 * 64);
             uint16_t *o1 = (uint16_t *)malloc(sizeof(uint16_t) * B * H * 64);
             float *l1 = (float *)malloc(sizeof(float) * B * H);
@@ -63,10 +65,7 @@ int main(void) {
             /* the streaming-read yardstick over a buffer that does not end on a 64-byte line */
             double gbs;
             unsigned long long chk;
-            {
-                const char *fs = getenv("FA_CPU_FORCE_SCALAR");
-                CHECK(fa_cpu_stream_read(k1, (long long)sizeof(uint16_t) * B * H * 1000 * 64 - 6, 5, 2, fs && fs[0] == '1', &gbs, &chk));
-            }
+            CHECK(fa_cpu_stream_read(k1, (long long)sizeof(uint16_t) * B * H * 1000 * 64 - 6, 5, 2, scalar_only, &gbs, &chk));
             free(q); free(k); free(v); free(w); free(o); free(lse); free(p); free(y);
             free(q1); free(k1); free(v1); free(o1); free(l1);
         }

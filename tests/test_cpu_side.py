@@ -122,13 +122,14 @@ def run_cpu_decode(q, k, v, scale, dtype, nthreads=0):
 
 
 @pytest.fixture(params=["avx512", "scalar"])
-def path(request, monkeypatch, lib):
+def path(request, lib):
     if request.param == "scalar":
-        monkeypatch.setenv("FA_CPU_FORCE_SCALAR", "1")
+        fc.fa_cpu_set_scalar(True)
         assert not fc.fa_cpu_has_avx512()
     elif not fc.fa_cpu_has_avx512():
         pytest.skip("this CPU has no AVX-512")
-    return request.param
+    yield request.param
+    fc.fa_cpu_set_scalar(False)
 
 
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])

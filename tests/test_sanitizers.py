@@ -22,9 +22,8 @@ def test_host_c_code_is_clean_under_asan_and_ubsan(tmp_path, force_scalar):
     # another library may be preloaded ahead of the sanitizer runtime on this machine; leak checking needs ptrace
     env["ASAN_OPTIONS"] = "verify_asan_link_order=0:detect_leaks=0:abort_on_error=0"
     env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
-    env["FA_CPU_FORCE_SCALAR"] = force_scalar
     env["OMP_NUM_THREADS"] = "4"
-    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    r = subprocess.run([exe, force_scalar], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "clean" in r.stdout
 
