@@ -506,6 +506,8 @@ def main():
                     help="time only the attention + output projection workload (for profiling runs)")
     ap.add_argument("--overlap-demo", action="store_true",
                     help="with --projection-only: also time the two-stream pipeline with the exchange stand-in")
+    ap.add_argument("--no-linear-overlap", action="store_true",
+                    help="fa_attn_linear keeps its projections on the caller's stream (for comparison runs)")
     ap.add_argument("--chunked-only", action="store_true",
                     help="time only the chunked-prefill workload through fa_fwd_splitkv (for profiling runs)")
     ap.add_argument("--sliding64-only", action="store_true",
@@ -547,6 +549,8 @@ def main():
     if args.fwd_mode:
         fa.fa_set_option(fa.FA_OPT_FWD_MODE, {"split": fa.FA_MODE_SPLIT, "wide": fa.FA_MODE_WIDE,
                                               "fold": fa.FA_MODE_WIDE_FOLD}[args.fwd_mode])
+    if args.no_linear_overlap:
+        fa.fa_set_option(fa.FA_OPT_LINEAR_OVERLAP, 0)
     cfg = I.CONFIGS[args.workload]
     if args.copy_calibration > 0:
         n = args.copy_calibration * (1 << 20) // 4

@@ -203,8 +203,17 @@ int fa_fwd_splitkv_plan(int B, int H, int Nq, int Nk, int D, int causal, int dty
  * a few row tiles so that each L2 fetches about as many bytes of o as of w; fa_set_option(
  * FA_OPT_LINEAR_PANEL, row tiles per panel) overrides that too (the order changes no result).
  *
- * fa_attn_linear -- every block in order on one stream: blocks of rows_per_block rows, the first
- * one half that size (nothing can overlap with the first block); rows_per_block <= 0: one block.
+ * fa_attn_linear -- every block in order: blocks of rows_per_block rows, the first one half that size
+ * (nothing can overlap with the first block); rows_per_block <= 0: one block.  With more than one block
+ * the projection of a block and the attention of the next touch different rows, so the projections are
+ * enqueued on a second stream of the library's own (default priority, one per device, created by the first
+ * such call on that device that is not under stream capture and kept until the process ends), each behind
+ * an event recorded on `stream` after its block's attention, and `stream` is made to wait for the second
+ * stream before the call returns: all of the call's work is ordered after what `stream` held before and
+ * before what is enqueued on it afterwards, as if it had all gone to `stream`, and a capture of `stream`
+ * records it as a fork and a join.  Calls on one device share that second stream: their enqueueing is
+ * serialised by a lock, their projections run in enqueue order.  Results are identical either way
+ * (fa_set_option(FA_OPT_LINEAR_OVERLAP, 0) keeps everything on `stream`).
  */
 int fa_attn_linear_block(const void *q, const void *k, const void *v, const void *w, void *o, float *lse,
                          float *y, int B, int H, int Nq, int Nk, int D, int N, float scale, int causal,
@@ -320,6 +329,8 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
  *   FA_OPT_DECODE_KERNEL : 0 or FA_AUTO: Nq = 1 runs the register-streaming kernel; 1: the tile kernels
  *   FA_OPT_LINEAR_TILE   : 128, 256 or FA_AUTO: token rows per workgroup tile of the projection
  *   FA_OPT_LINEAR_PANEL  : >= 1 or FA_AUTO: row tiles per panel of the projection's tile order
+ *   FA_OPT_LINEAR_OVERLAP: 1 or FA_AUTO: fa_attn_linear runs the projections on its second stream; 0: everything
+ *                          on the caller's stream
  *
  * Returns the option's previous value (FA_AUTO = -1 if it was never set), or FA_ERR_OPTION for an
  * unknown option or a value outside the list above (nothing is changed then).
@@ -329,6 +340,7 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
 #define FA_OPT_DECODE_KERNEL 1
 #define FA_OPT_LINEAR_TILE   2
 #define FA_OPT_LINEAR_PANEL  3
+#define FA_OPT_LINEAR_OVERLAP 4
 int fa_set_option(int option, int value);
 
 /* static, never-freed description of an FA_ERR_* code */

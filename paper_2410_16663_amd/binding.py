@@ -29,6 +29,7 @@ FA_OPT_FWD_MODE = 0
 FA_OPT_DECODE_KERNEL = 1
 FA_OPT_LINEAR_TILE = 2
 FA_OPT_LINEAR_PANEL = 3
+FA_OPT_LINEAR_OVERLAP = 4
 FA_TILE_SKIP = 0
 FA_TILE_FULL = 1
 FA_TILE_PARTIAL = 2

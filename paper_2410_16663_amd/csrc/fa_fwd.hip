@@ -24,9 +24,9 @@
 //  * this file -- the host side: argument checks, choice of decomposition, launch shapes, the C ABI.
 //
 // gfx950 mapping common to all variants of the attention kernel (this library's own design):
-//  * one wavefront owns 32 query rows; a workgroup is 8 wavefronts, two per SIMD.  A wavefront
-//    cannot issue vector work while its own matrix instruction runs, so overlap of the matrix
-//    and vector units comes from the two wavefronts of a SIMD being in different phases; they
+//  * one wavefront owns 32 query rows; a workgroup is 8 wavefronts, two per SIMD.  Each wavefront
+//    runs a tile as three clusters (logits, softmax, second product); overlap of the matrix and
+//    vector units comes mostly from the two wavefronts of a SIMD being in different clusters; they
 //    run free between the one workgroup barrier per tile.
 //  * logits are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: keys on the
 //    M side (A operand, read from LDS with ds_read_b128), queries on the N side (B
@@ -116,7 +116,7 @@ hipError_t launch_decode_masked(const FaParams &p, int heads, hipStream_t stream
 thread_local int g_last_hip_error = 0;
 
 // fa_set_option's values (FA_AUTO: the library chooses).  Every entry point reads each of them at most once per call.
-std::atomic<int> g_options[4] = {{FA_AUTO}, {FA_AUTO}, {FA_AUTO}, {FA_AUTO}};
+std::atomic<int> g_options[5] = {{FA_AUTO}, {FA_AUTO}, {FA_AUTO}, {FA_AUTO}, {FA_AUTO}};
 int option(int which) { return g_options[which].load(std::memory_order_relaxed); }
 
 // Shape checks shared by fa_fwd and fa_fwd_plan; everything here runs before any HIP call.
@@ -605,9 +605,10 @@ int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float
     return FA_OK;
 }
 
-int fa_attn_linear_block(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y,
-                         int B, int H, int Nq, int Nk, int D, int N, float scale, int causal, int dtype,
-                         int row_first, int row_count, void *stream) {
+namespace {
+
+int check_attn_linear(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y,
+                      int B, int H, int Nq, int Nk, int D, int N, float scale, int dtype, int row_first, int row_count) {
     if (!q || !k || !v || !w || !o || !lse || !y) return FA_ERR_NULL;
     const int rc = check_shape(B, H, Nq, Nk, D, dtype);
     if (rc != FA_OK) return rc;
@@ -617,10 +618,13 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
     if (!isfinite(scale)) return FA_ERR_SCALE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)w) & 15) return FA_ERR_ALIGN;
     if (((uintptr_t)lse | (uintptr_t)y) & 3) return FA_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
+    return FA_OK;
+}
 
-    // 1. attention of the block's rows, every head: a launch over row_count rows whose diagonal is shifted
-    //    by row_first; q, o, lse keep the full tensors' head pitch
+// attention of one block of rows, every head: a launch over row_count rows whose diagonal is shifted by
+// row_first; q, o, lse keep the full tensors' head pitch.  Arguments already checked.
+int block_attention(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
+                    int D, float scale, int causal, int dtype, int row_first, int row_count, hipStream_t st) {
     {
         const int mode = choose_mode(B, H, row_count, D, causal);
         const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
@@ -636,7 +640,12 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
             return FA_ERR_LAUNCH;
         }
     }
-    // 2. the block's rows of y = (heads side by side) x w
+    return FA_OK;
+}
+
+// the block's rows of y = (heads side by side) x w.  Arguments already checked.
+int block_projection(const void *w, const void *o, float *y, int B, int H, int Nq, int D, int N, int dtype,
+                     int row_first, int row_count, hipStream_t st) {
     {
         LinParams lp;
         lp.o = (const uint16_t *)o;
@@ -675,20 +684,108 @@ int fa_attn_linear_block(const void *q, const void *k, const void *v, const void
     return FA_OK;
 }
 
+// fa_attn_linear's second stream (default priority) and the two events that tie it to the caller's stream, one
+// set per device, created on the first call that may create them (not under stream capture) and kept until the
+// process ends.  `busy` serialises the enqueueing of calls that share them.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t attn_done = nullptr, joined = nullptr;
+    bool ready = false;
+    std::mutex busy;
+};
+SideStream g_side[64];
+
+}  // namespace
+
+int fa_attn_linear_block(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y,
+                         int B, int H, int Nq, int Nk, int D, int N, float scale, int causal, int dtype,
+                         int row_first, int row_count, void *stream) {
+    int rc = check_attn_linear(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, dtype, row_first, row_count);
+    if (rc != FA_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = block_attention(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, row_first, row_count, st);
+    if (rc != FA_OK) return rc;
+    return block_projection(w, o, y, B, H, Nq, D, N, dtype, row_first, row_count, st);
+}
+
 int fa_attn_linear(const void *q, const void *k, const void *v, const void *w, void *o, float *lse, float *y, int B,
                    int H, int Nq, int Nk, int D, int N, float scale, int causal, int dtype, int rows_per_block,
                    void *stream) {
     if (rows_per_block <= 0 || rows_per_block >= Nq)
         return fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, 0, Nq, stream);
+    int rc = check_attn_linear(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, dtype, 0, Nq);
+    if (rc != FA_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+
+    // The projection of block i and the attention of block i + 1 touch different rows, so the projections go to
+    // a second stream behind an event recorded after each attention launch: the tail of one kernel (its last
+    // workgroups, its stores) then overlaps the head of the next instead of leaving compute units idle between
+    // ten short launches.  The caller's stream waits for the second stream at the end, so to the caller the call
+    // behaves as if everything had been enqueued on `stream`.
+    SideStream *side = nullptr;
+    std::unique_lock<std::mutex> hold;
+    if (option(FA_OPT_LINEAR_OVERLAP) != 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess || dev < 0 || dev >= 64) {
+            g_last_hip_error = (int)e;
+            return FA_ERR_LAUNCH;
+        }
+        hold = std::unique_lock<std::mutex>(g_side[dev].busy);
+        if (!g_side[dev].ready) {
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            e = hipStreamIsCapturing(st, &cap);
+            if (e != hipSuccess) {
+                g_last_hip_error = (int)e;
+                return FA_ERR_LAUNCH;
+            }
+            if (cap == hipStreamCaptureStatusNone) {     // nothing is created while a capture is in progress
+                SideStream &n = g_side[dev];
+                e = hipStreamCreateWithFlags(&n.stream, hipStreamNonBlocking);
+                if (e == hipSuccess) e = hipEventCreateWithFlags(&n.attn_done, hipEventDisableTiming);
+                if (e == hipSuccess) e = hipEventCreateWithFlags(&n.joined, hipEventDisableTiming);
+                if (e != hipSuccess) {
+                    g_last_hip_error = (int)e;
+                    return FA_ERR_LAUNCH;
+                }
+                n.ready = true;
+            }
+        }
+        if (g_side[dev].ready) side = &g_side[dev];
+        else hold.unlock();
+    }
+
     // the first block is half size (section 4.2: nothing overlaps with the first block's computation)
-    int first = rows_per_block / 2 > 0 ? rows_per_block / 2 : rows_per_block;
-    for (int r = 0; r < Nq;) {
+    const int first = rows_per_block / 2 > 0 ? rows_per_block / 2 : rows_per_block;
+    bool forked = false;
+    for (int r = 0; r < Nq && rc == FA_OK;) {
         const int n = r == 0 ? first : (Nq - r < rows_per_block ? Nq - r : rows_per_block);
-        const int rc = fa_attn_linear_block(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dtype, r, n, stream);
-        if (rc != FA_OK) return rc;
+        rc = block_attention(q, k, v, o, lse, B, H, Nq, Nk, D, scale, causal, dtype, r, n, st);
+        if (rc != FA_OK) break;
+        hipStream_t lin_stream = st;
+        if (side) {
+            hipError_t e = hipEventRecord(side->attn_done, st);
+            if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->attn_done, 0);
+            if (e != hipSuccess) {
+                g_last_hip_error = (int)e;
+                rc = FA_ERR_LAUNCH;
+                break;
+            }
+            forked = true;
+            lin_stream = side->stream;
+        }
+        rc = block_projection(w, o, y, B, H, Nq, D, N, dtype, r, n, lin_stream);
         r += n;
     }
-    return FA_OK;
+    if (forked) {      // also after an error: the second stream must rejoin (a capture could not end otherwise)
+        hipError_t e = hipEventRecord(side->joined, side->stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st, side->joined, 0);
+        if (e != hipSuccess && rc == FA_OK) {
+            g_last_hip_error = (int)e;
+            rc = FA_ERR_LAUNCH;
+        }
+    }
+    return rc;
 }
 
 int fa_mask_tile_class(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int row_first, int row_last, int key_first) {
@@ -734,6 +831,7 @@ int fa_set_option(int opt, int value) {
         case FA_OPT_DECODE_KERNEL: ok = ok || value == 0 || value == 1; break;
         case FA_OPT_LINEAR_TILE: ok = ok || value == 128 || value == 256; break;
         case FA_OPT_LINEAR_PANEL: ok = ok || value >= 1; break;
+        case FA_OPT_LINEAR_OVERLAP: ok = ok || value == 0 || value == 1; break;
         default: return FA_ERR_OPTION;
     }
     if (!ok) return FA_ERR_OPTION;

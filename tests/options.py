@@ -26,6 +26,12 @@ def set_linear_panel(tiles):
     fa.fa_set_option(fa.FA_OPT_LINEAR_PANEL, fa.FA_AUTO if tiles is None else int(tiles))
 
 
+def set_linear_overlap(on):
+    """True / False / None (the library's default: overlapped)"""
+    fa.fa_set_option(fa.FA_OPT_LINEAR_OVERLAP, fa.FA_AUTO if on is None else int(bool(on)))
+
+
 def reset_all():
-    for opt in (fa.FA_OPT_FWD_MODE, fa.FA_OPT_DECODE_KERNEL, fa.FA_OPT_LINEAR_TILE, fa.FA_OPT_LINEAR_PANEL):
+    for opt in (fa.FA_OPT_FWD_MODE, fa.FA_OPT_DECODE_KERNEL, fa.FA_OPT_LINEAR_TILE, fa.FA_OPT_LINEAR_PANEL,
+                fa.FA_OPT_LINEAR_OVERLAP):
         fa.fa_set_option(opt, fa.FA_AUTO)

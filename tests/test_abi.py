@@ -166,11 +166,11 @@ def test_options_take_only_their_values_and_return_the_previous_one(lib):
     assert fa.fa_fwd_plan(8, 32, 8192, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE
     L = fa.load()
     for opt, bad in ((fa.FA_OPT_FWD_MODE, 7), (fa.FA_OPT_FWD_MODE, fa.FA_MODE_STREAM), (fa.FA_OPT_DECODE_KERNEL, 2),
-                     (fa.FA_OPT_LINEAR_TILE, 64), (fa.FA_OPT_LINEAR_PANEL, 0), (9, 0), (-1, 0)):
+                     (fa.FA_OPT_LINEAR_TILE, 64), (fa.FA_OPT_LINEAR_PANEL, 0), (fa.FA_OPT_LINEAR_OVERLAP, 2), (9, 0), (-1, 0)):
         assert L.fa_set_option(opt, bad) == fa.FA_ERR_OPTION
     with pytest.raises(fa.FaError):
         fa.fa_set_option(fa.FA_OPT_LINEAR_TILE, 100)
-    for opt in range(4):
+    for opt in range(5):
         assert L.fa_set_option(opt, fa.FA_AUTO) == fa.FA_AUTO       # the failed calls changed nothing
 
 

@@ -107,6 +107,39 @@ def test_tile_order_changes_no_bit(monkeypatch, tile):
         assert np.array_equal(r, y)
 
 
+def test_projections_on_the_second_stream_change_no_bit(tile):
+    """fa_attn_linear enqueues the projections on a stream of its own behind events (FA_OPT_LINEAR_OVERLAP of
+    include/fa.h): the same kernels on the same data, so o, lse and y are those of the one-stream call bit for
+    bit, call after call, and work enqueued on the caller's stream afterwards sees the finished y."""
+    import torch
+    from paper_2410_16663_amd import binding as fa
+    print(f"case attn_linear second stream tile={tile}", flush=True)
+    rng = np.random.default_rng(604)
+    B, H, Nq, Nk, D, N = 2, 3, 1100, 1100, 128, 512
+    q, k, v, w = make(rng, B, H, Nq, Nk, D, N, I.BF16)
+    options.set_linear_overlap(False)
+    o0, lse0, y0 = run_attn_linear(q, k, v, w, 0.09, True, I.BF16, rows_per_block=256)
+    options.set_linear_overlap(None)
+    for _ in range(3):
+        o1, lse1, y1 = run_attn_linear(q, k, v, w, 0.09, True, I.BF16, rows_per_block=256)
+        assert np.array_equal(o0, o1) and np.array_equal(lse0, lse1) and np.array_equal(y0, y1)
+    # the caller's stream is ordered after the second stream: a reduction enqueued right after the call, with no
+    # synchronisation in between, reads the complete y
+    dev = torch.device("cuda:0")
+    tq, tk, tv, tw = (torch.from_numpy(a.view(np.int16)).to(dev) for a in (q, k, v, w))
+    to = torch.zeros((B, H, Nq, D), dtype=torch.int16, device=dev)
+    tl = torch.zeros((B, H, Nq), dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            ty = torch.full((B, Nq, N), float("nan"), dtype=torch.float32, device=dev)
+            fa.fa_attn_linear(tq, tk, tv, tw, to, tl, ty, B, H, Nq, Nk, D, N, 0.09, 1, I.BF16, 256, side.cuda_stream)
+            total = ty.double().sum()
+            ty.fill_(float("nan"))            # enqueued after the call too: must not overtake its projections
+            assert abs(total.item() - y0.astype(np.float64).sum()) < 1e-6 * np.abs(y0).sum()
+    side.synchronize()
+
+
 def test_one_block_gives_fa_fwd_bit_for_bit_and_exact_projections():
     """The whole problem as one block runs the same attention launch as fa_fwd; with w = identity columns the
     projection returns o itself (products with 1 and 0, fp32 sums of one term)."""
