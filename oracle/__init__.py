@@ -45,7 +45,7 @@ def _load():
         lib.fa_oracle_fwd_masked.restype = ctypes.c_int
         lib.fa_oracle_fwd_masked.argtypes = [u16p, u16p, u16p, f64p, f64p] + [ctypes.c_int] * 5 + [
             ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int32),
-            ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
+            ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
         lib.fa_oracle_attn_linear.restype = ctypes.c_int
         lib.fa_oracle_attn_linear.argtypes = [u16p, u16p, u16p, u16p, f64p] + [ctypes.c_int] * 6 + [
             ctypes.c_double, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, ctypes.c_int]
@@ -102,11 +102,12 @@ def attention_fwd(q_bits, k_bits, v_bits, scale, causal, dtype, rows=None, nthre
 
 
 def attention_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None, rows=None,
-                         nthreads=0):
+                         nthreads=0, diag_from_kv_len=False):
     """Oracle forward under a mask given by a descriptor: key j is visible to row i of batch entry b iff
     ``j < kv_len[b]`` (all keys if ``kv_len`` is None) and (``j < prefix`` or
-    ``diag - left <= j <= diag + right``), ``diag = i + Nk - Nq``; a negative ``left`` / ``right`` is no limit.
-    Same shapes and return values as :func:`attention_fwd`."""
+    ``diag - left <= j <= diag + right``), ``diag = i + Nk - Nq``, or ``i + kv_len[b] - Nq`` with
+    ``diag_from_kv_len`` (the queries are the last Nq positions of each entry's own sequence); a negative
+    ``left`` / ``right`` is no limit.  Same shapes and return values as :func:`attention_fwd`."""
     lib = _load()
     B, H, Nq, D = q_bits.shape
     Nk = k_bits.shape[2]
@@ -131,8 +132,8 @@ def attention_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1
         lp = _ptr(kv_len, ctypes.c_int32)
     rc = lib.fa_oracle_fwd_masked(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16), _ptr(v, ctypes.c_uint16),
                                   _ptr(o, ctypes.c_double), _ptr(lse, ctypes.c_double), B, H, Nq, Nk, D,
-                                  float(scale), int(left), int(right), int(prefix), lp, int(dtype), rp, nr,
-                                  int(nthreads))
+                                  float(scale), int(left), int(right), int(prefix), lp, int(bool(diag_from_kv_len)),
+                                  int(dtype), rp, nr, int(nthreads))
     if rc != 0:
         raise RuntimeError(f"fa_oracle_fwd_masked failed with code {rc}")
     return o, lse

@@ -205,15 +205,19 @@ int fa_oracle_probs(const uint16_t *q, const uint16_t *k, double *p, int B, int 
  *     and ( j < prefix                        (a prefix every row sees, prefix-LM)
  *           or  diag_i - left <= j <= diag_i + right )   with diag_i = i + (Nk - Nq),
  *                                              a negative left / right meaning "no limit"
+ * diag_from_kv_len != 0 puts the diagonal of batch entry b at its own last key instead of the last
+ * of the Nk: diag_i = i + (klen_b - Nq), i.e. the Nq queries are the last Nq positions of a sequence
+ * of klen_b tokens (appendix C's decoding step, where the new token's query attends its own
+ * sequence's cache, for a batch whose caches have different lengths).
  * left < 0, right = 0, prefix = 0, no kv_len is the causal mask; left < 0, right < 0 is no mask.
  * Same plain row-at-a-time evaluation as fa_oracle_fwd, written out on its own: the logits of
  * the visible keys, their maximum, the weights, the weighted sum.
  */
 static int key_is_visible(int64_t i, int64_t j, int Nq, int Nk, int64_t left, int64_t right,
-                          int64_t prefix, int64_t klen) {
+                          int64_t prefix, int64_t klen, int diag_from_kv_len) {
     if (j >= klen) return 0;
     if (j < prefix) return 1;
-    int64_t diag = i + ((int64_t)Nk - (int64_t)Nq);
+    int64_t diag = i + ((diag_from_kv_len ? klen : (int64_t)Nk) - (int64_t)Nq);
     if (left >= 0 && j < diag - left) return 0;
     if (right >= 0 && j > diag + right) return 0;
     return 1;
@@ -221,8 +225,8 @@ static int key_is_visible(int64_t i, int64_t j, int Nq, int Nk, int64_t left, in
 
 int fa_oracle_fwd_masked(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
                          int B, int H, int Nq, int Nk, int D, double scale, int64_t left, int64_t right,
-                         int64_t prefix, const int32_t *kv_len, int dtype, const int64_t *rows,
-                         int64_t nrows, int nthreads) {
+                         int64_t prefix, const int32_t *kv_len, int diag_from_kv_len, int dtype,
+                         const int64_t *rows, int64_t nrows, int nthreads) {
     int err = bad_args(q, k, v, B, H, Nq, Nk, D, dtype);
     if (err) return err;
     if (!o || !lse) return -1;
@@ -263,7 +267,7 @@ int fa_oracle_fwd_masked(const uint16_t *q, const uint16_t *k, const uint16_t *v
             double m = -INFINITY;
             int64_t count = 0;
             for (int64_t j = 0; j < Nk; ++j) {
-                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen)) continue;
+                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen, diag_from_kv_len)) continue;
                 double dot = 0.0;
                 for (int d = 0; d < D; ++d) dot += widen(q_row[d], dtype) * widen(k_head[j * D + d], dtype);
                 s[j] = scale * dot;
@@ -278,7 +282,7 @@ int fa_oracle_fwd_masked(const uint16_t *q, const uint16_t *k, const uint16_t *v
             /* weights, their sum, the weighted sum of the value rows */
             double l = 0.0;
             for (int64_t j = 0; j < Nk; ++j) {
-                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen)) continue;
+                if (!key_is_visible(i, j, Nq, Nk, left, right, prefix, klen, diag_from_kv_len)) continue;
                 double w = exp(s[j] - m);
                 l += w;
                 for (int d = 0; d < D; ++d) o_row[d] += w * widen(v_head[j * D + d], dtype);

@@ -12,7 +12,7 @@ int fa_oracle_fwd(const uint16_t *, const uint16_t *, const uint16_t *, double *
                   double, int, int, const int64_t *, int64_t, int);
 int fa_oracle_probs(const uint16_t *, const uint16_t *, double *, int, int, int, int, int, double, int, int, int64_t);
 int fa_oracle_fwd_masked(const uint16_t *, const uint16_t *, const uint16_t *, double *, double *, int, int, int, int,
-                         int, double, int64_t, int64_t, int64_t, const int32_t *, int, const int64_t *, int64_t, int);
+                         int, double, int64_t, int64_t, int64_t, const int32_t *, int, int, const int64_t *, int64_t, int);
 int fa_oracle_attn_linear(const uint16_t *, const uint16_t *, const uint16_t *, const uint16_t *, double *, int, int,
                           int, int, int, int, double, int, int, const int64_t *, int64_t, int);
 int fa_coop_plan_bytes(double, double, double, double, double, int, int, int *, int *);
@@ -49,8 +49,8 @@ int main(int argc, char **argv) {
             CHECK(fa_oracle_fwd(q, k, v, o, lse, B, H, Nq, Nk, D, 0.25, causal, dtype, rows, 3, 1));
             CHECK(fa_oracle_probs(q, k, p, B, H, Nq, Nk, D, 0.25, causal, dtype, 17));
             const int32_t lens[2] = {53, 7};
-            CHECK(fa_oracle_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, 0.25, 9, causal ? 0 : 4, 3, lens, dtype, NULL, 0, 2));
-            CHECK(fa_oracle_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, 0.25, -1, -1, 0, NULL, dtype, rows, 3, 2));
+            CHECK(fa_oracle_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, 0.25, 9, causal ? 0 : 4, 3, lens, causal, dtype, NULL, 0, 2));
+            CHECK(fa_oracle_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, 0.25, -1, -1, 0, NULL, 0, dtype, rows, 3, 2));
             CHECK(fa_oracle_attn_linear(q, k, v, w, y, B, H, Nq, Nk, D, N, 0.25, causal, dtype, NULL, 0, 2));
             /* Nq > Nk causal: rows without keys */
             CHECK(fa_oracle_fwd(q, k, v, o, lse, B, H, Nq, 20, D, 0.25, 1, dtype, NULL, 0, 2));

@@ -176,6 +176,71 @@ def test_zero_queries_count_the_visible_keys(oracle):
             np.testing.assert_allclose(o[b, 0, i], V[b, 0, js].mean(axis=0), rtol=1e-13, atol=1e-15)
 
 
+def test_diagonal_at_each_entrys_own_last_key_equals_the_truncated_problem(oracle):
+    """diag_from_kv_len: the queries are the last Nq positions of each entry's own kv_len[b] keys, so entry b is
+    the same descriptor (without key lengths) applied to that entry's first kv_len[b] keys alone -- the function
+    pinned above, on inputs cut by numpy."""
+    rng = np.random.default_rng(309)
+    q, k, v = rand_qkv(rng, 4, 2, 3, 11, 4, I.BF16)
+    lens = [11, 7, 3, 1]
+    for left, right, prefix in ((-1, 0, 0), (2, 0, 0), (0, 0, 0), (1, 1, 2), (4, -1, 1), (-1, -1, 0)):
+        o, lse = oracle.attention_fwd_masked(q, k, v, 0.6, I.BF16, left, right, prefix, lens, diag_from_kv_len=True)
+        for b, L in enumerate(lens):
+            ob, lb = oracle.attention_fwd_masked(q[b:b + 1], k[b:b + 1, :, :L], v[b:b + 1, :, :L], 0.6, I.BF16, left,
+                                                 right, prefix)
+            np.testing.assert_allclose(o[b:b + 1], ob, rtol=1e-13, atol=1e-15)
+            np.testing.assert_array_equal(np.isneginf(lse[b:b + 1]), np.isneginf(lb))
+            fin = np.isfinite(lb)
+            np.testing.assert_allclose(lse[b:b + 1][fin], lb[fin], rtol=1e-13, atol=1e-15)
+    # without key lengths the flag changes nothing
+    a = oracle.attention_fwd_masked(q, k, v, 0.6, I.BF16, 2, 0, 1)
+    c = oracle.attention_fwd_masked(q, k, v, 0.6, I.BF16, 2, 0, 1, diag_from_kv_len=True)
+    np.testing.assert_array_equal(a[0], c[0])
+    np.testing.assert_array_equal(a[1], c[1])
+
+
+def test_decoding_step_with_a_window_over_caches_of_different_lengths(oracle):
+    """Appendix C's decoding step (one query, the new token) for a batch of caches of different lengths under a
+    sliding window of W keys: with Q = 0 the query of entry b weighs the last min(W, L_b) of ITS keys equally --
+    lse = ln min(W, L_b), o = their mean -- wherever the cache ends inside the Nk allocated rows.  Without the
+    flag the window hangs on key Nk - 1 and misses the short caches altogether."""
+    rng = np.random.default_rng(310)
+    Nk, D, W = 20, 4, 5
+    _, k, v = rand_qkv(rng, 4, 2, 1, Nk, D, I.F16)
+    q = np.zeros((4, 2, 1, D), dtype=np.uint16)
+    lens = [20, 12, 3, 0]
+    o, lse = oracle.attention_fwd_masked(q, k, v, 1.0, I.F16, W - 1, 0, 0, lens, diag_from_kv_len=True)
+    V = I.bits_to_f64(v, I.F16)
+    for b, L in enumerate(lens):
+        n = min(W, L)
+        if n == 0:
+            assert np.isneginf(lse[b]).all() and (o[b] == 0).all()
+            continue
+        np.testing.assert_allclose(lse[b, :, 0], math.log(n), rtol=1e-14)
+        np.testing.assert_allclose(o[b, :, 0], V[b, :, L - n:L].mean(axis=1), rtol=1e-13, atol=1e-15)
+    o2, lse2 = oracle.attention_fwd_masked(q, k, v, 1.0, I.F16, W - 1, 0, 0, lens)
+    np.testing.assert_allclose(lse2[0, :, 0], math.log(W), rtol=1e-14)
+    assert np.isneginf(lse2[1:]).all()                       # keys 15..19 are padding for the shorter caches
+
+
+def test_diagonal_flag_against_explicit_matrices(oracle):
+    """The same flag against keep-matrices written with numpy's triangle routines, offset L_b - Nq per entry."""
+    rng = np.random.default_rng(311)
+    B, H, Nq, Nk, D = 3, 2, 4, 9, 4
+    q, k, v = rand_qkv(rng, B, H, Nq, Nk, D, I.F16)
+    lens = [9, 6, 2]
+    for left, right, prefix in ((1, 0, 0), (-1, 0, 1), (2, 1, 0)):
+        keep = np.zeros((B, Nq, Nk), dtype=bool)
+        for b, L in enumerate(lens):
+            keep[b, :, :L] = band_matrix(Nq, L, left, right, prefix, L)
+        o_ref, lse_ref = matrix_attention(q, k, v, 0.5, I.F16, keep)
+        o, lse = oracle.attention_fwd_masked(q, k, v, 0.5, I.F16, left, right, prefix, lens, diag_from_kv_len=True)
+        np.testing.assert_allclose(o, o_ref, rtol=1e-12, atol=1e-14)
+        fin = np.isfinite(lse_ref)
+        np.testing.assert_array_equal(np.isneginf(lse), ~fin)
+        np.testing.assert_allclose(lse[fin], lse_ref[fin], rtol=1e-12, atol=1e-14)
+
+
 def test_row_subset_and_bad_arguments(oracle):
     rng = np.random.default_rng(308)
     q, k, v = rand_qkv(rng, 2, 2, 6, 9, 4, I.F16)
