@@ -239,6 +239,12 @@ int fa_attn_linear(const void *q, const void *k, const void *v, const void *w, v
  *                  window of W keys, (W, W) a symmetric local window
  *   prefix       : >= 0; the first `prefix` keys are visible to every row whatever the window
  *                  (prefix-LM: a bidirectional prompt followed by causal text)
+ *   diag_from_kv_len : 0: diag_i as above.  1: diag_i = i + (klen_b - Nq) -- the Nq queries of entry b are
+ *                  the LAST Nq positions of its own klen_b keys, wherever those end inside the Nk
+ *                  allocated rows: appendix C's decoding step (or a chunk of a chunked prefill) for a
+ *                  batch of caches of different lengths, where a causal limit or a sliding window must
+ *                  hang on each sequence's own last token.  Any other value: FA_ERR_MASK.  Set every
+ *                  member (or zero the struct first): the member occupies what used to be padding
  *   kv_len       : DEVICE pointer to B int32 (4-byte aligned) or NULL: keys at and after
  *                  kv_len[b] are padding; values are clamped to 0..Nk on the device
  */
@@ -246,6 +252,7 @@ typedef struct fa_mask {
     int window_left;
     int window_right;
     int prefix;
+    int diag_from_kv_len;
     const int *kv_len;
 } fa_mask_t;
 
@@ -270,7 +277,8 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
  * visible keys of every (batch, head) cut into `nsplit` equal shares as in fa_fwd_splitkv: the call for small
  * batches of caches of different lengths (appendix C's decoding equations with section 4.1's generated mask),
  * where B * H workgroups alone cannot fill the chip.  The query sits on the last key (diag = Nk - 1), so
- * (-1, 0) lets it see kv_len[b] keys, (W - 1, 0) the last W of the Nk.  Each share is counted along the
+ * (-1, 0) lets it see kv_len[b] keys, (W - 1, 0) the last W of the Nk; with diag_from_kv_len = 1 it sits on
+ * key kv_len[b] - 1 and (W - 1, 0) is the last W keys of each cache.  Each share is counted along the
  * prefix and the window laid end to end, so entries with few keys are split as evenly as entries with many.
  *
  *   nsplit, workspace, workspace_bytes : as for fa_fwd_splitkv with Nq = 1; fa_fwd_splitkv_plan(B, H, 1, Nk, D,
@@ -288,7 +296,7 @@ int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float
 /*
  * The tile classification and the workgroup's walk, callable on the host (the kernel runs the
  * same code): for tests and for callers that want to know the work a mask leaves.
- * kv_len here is ONE batch entry's key count (host int, 0..Nk); mask->kv_len is not read.
+ * kv_len here is ONE batch entry's key count (host int, 0..Nk); mask->kv_len is not read (mask->diag_from_kv_len is).
  *
  * fa_mask_tile_class: rows row_first..row_last against keys key_first..key_first+63 (key_first a
  *   multiple of 64).  Returns

@@ -67,7 +67,7 @@ class FaSplitKvPlan(ctypes.Structure):
 class FaMask(ctypes.Structure):
     """fa_mask_t of include/fa.h (kv_len is a device address or 0)."""
     _fields_ = [("window_left", ctypes.c_int), ("window_right", ctypes.c_int), ("prefix", ctypes.c_int),
-                ("kv_len", ctypes.c_void_p)]
+                ("diag_from_kv_len", ctypes.c_int), ("kv_len", ctypes.c_void_p)]
 
 
 class FaError(RuntimeError):
@@ -250,45 +250,48 @@ def fa_attn_linear(q, k, v, w, o, lse, y, B, H, Nq, Nk, D, N, scale, causal, dty
         raise FaError(rc)
 
 
-def _mask(left, right, prefix, kv_len):
-    return FaMask(int(left), int(right), int(prefix), _addr(kv_len) or None)
+def _mask(left, right, prefix, kv_len, diag_from_kv_len=0):
+    return FaMask(int(left), int(right), int(prefix), int(diag_from_kv_len), _addr(kv_len) or None)
 
 
-def fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0) -> int:
+def fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0,
+                      diag_from_kv_len=0) -> int:
     """Call fa_fwd_masked (mask fields passed one by one) and return its status code unchanged."""
-    m = _mask(left, right, prefix, kv_len)
+    m = _mask(left, right, prefix, kv_len, diag_from_kv_len)
     return load().fa_fwd_masked(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nq),
                                 int(Nk), int(D), float(scale), ctypes.byref(m), int(dtype), _addr(stream))
 
 
-def fa_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0) -> None:
+def fa_fwd_masked(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream=0,
+                  diag_from_kv_len=0) -> None:
     """fa_fwd_masked of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
-    rc = fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream)
+    rc = fa_fwd_masked_raw(q, k, v, o, lse, B, H, Nq, Nk, D, scale, left, right, prefix, kv_len, dtype, stream,
+                           diag_from_kv_len)
     if rc != FA_OK:
         raise FaError(rc)
 
 
 def fa_decode_masked_raw(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit, workspace,
-                         workspace_bytes, stream=0) -> int:
+                         workspace_bytes, stream=0, diag_from_kv_len=0) -> int:
     """Call fa_decode_masked (mask fields passed one by one) and return its status code unchanged."""
-    m = _mask(left, right, prefix, kv_len)
+    m = _mask(left, right, prefix, kv_len, diag_from_kv_len)
     return load().fa_decode_masked(_addr(q), _addr(k), _addr(v), _addr(o), _addr(lse), int(B), int(H), int(Nk), int(D),
                                    float(scale), ctypes.byref(m), int(dtype), int(nsplit), _addr(workspace),
                                    int(workspace_bytes), _addr(stream))
 
 
 def fa_decode_masked(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit, workspace,
-                     workspace_bytes, stream=0) -> None:
+                     workspace_bytes, stream=0, diag_from_kv_len=0) -> None:
     """fa_decode_masked of include/fa.h; raises FaError on a negative status. Asynchronous on ``stream``."""
     rc = fa_decode_masked_raw(q, k, v, o, lse, B, H, Nk, D, scale, left, right, prefix, kv_len, dtype, nsplit,
-                              workspace, workspace_bytes, stream)
+                              workspace, workspace_bytes, stream, diag_from_kv_len)
     if rc != FA_OK:
         raise FaError(rc)
 
 
-def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last, key_first) -> int:
+def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last, key_first, diag_from_kv_len=0) -> int:
     """fa_mask_tile_class of include/fa.h (host only; kv_len is one batch entry's key count)."""
-    m = _mask(left, right, prefix, None)
+    m = _mask(left, right, prefix, None, diag_from_kv_len)
     rc = load().fa_mask_tile_class(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last),
                                    int(key_first))
     if rc < 0:
@@ -296,9 +299,9 @@ def fa_mask_tile_class(left, right, prefix, kv_len, Nq, Nk, row_first, row_last,
     return rc
 
 
-def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last):
+def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last, diag_from_kv_len=0):
     """fa_mask_tile_walk of include/fa.h (host only): the list of tile indices, in the order walked."""
-    m = _mask(left, right, prefix, None)
+    m = _mask(left, right, prefix, None, diag_from_kv_len)
     count = ctypes.c_int()
     args = (ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(row_first), int(row_last))
     rc = load().fa_mask_tile_walk(*args, None, 0, ctypes.byref(count))
@@ -311,9 +314,9 @@ def fa_mask_tile_walk(left, right, prefix, kv_len, Nq, Nk, row_first, row_last):
     return list(tiles[:count.value])
 
 
-def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_row_last, row_first, row_last):
+def fa_mask_interior_run(left, right, prefix, kv_len, Nq, Nk, wg_row_first, wg_row_last, row_first, row_last, diag_from_kv_len=0):
     """fa_mask_interior_run of include/fa.h (host only): (first, count) in positions of the workgroup's walk."""
-    m = _mask(left, right, prefix, None)
+    m = _mask(left, right, prefix, None, diag_from_kv_len)
     first, count = ctypes.c_int(), ctypes.c_int()
     rc = load().fa_mask_interior_run(ctypes.byref(m), int(kv_len), int(Nq), int(Nk), int(wg_row_first),
                                      int(wg_row_last), int(row_first), int(row_last), ctypes.byref(first),

@@ -297,6 +297,7 @@ FaParams base_params(const void *q, const void *k, const void *v, void *o, float
     p.part_o = nullptr;
     p.part_ml = nullptr;
     p.left = p.right = p.prefix = 0;
+    p.anchor = 0;
     p.kv_len = nullptr;
     return p;
 }
@@ -308,7 +309,8 @@ int mask_geometry(const fa_mask_t *mask, int klen, int Nq, int Nk, MaskGeom *g) 
     if ((long long)Nq + Nk >= MASK_NO_LIMIT) return FA_ERR_SHAPE;   // window arithmetic stays inside int
     if (mask->prefix < 0) return FA_ERR_MASK;
     if (klen < 0 || klen > Nk) return FA_ERR_MASK;
-    g->off = Nk - Nq;
+    if (mask->diag_from_kv_len != 0 && mask->diag_from_kv_len != 1) return FA_ERR_MASK;
+    g->off = (mask->diag_from_kv_len ? klen : Nk) - Nq;
     g->left = mask->window_left < 0 || mask->window_left > MASK_NO_LIMIT ? MASK_NO_LIMIT : mask->window_left;
     g->right = mask->window_right < 0 || mask->window_right > MASK_NO_LIMIT ? MASK_NO_LIMIT : mask->window_right;
     g->pfx = mask->prefix < klen ? mask->prefix : klen;
@@ -533,6 +535,7 @@ int fa_fwd_masked(const void *q, const void *k, const void *v, void *o, float *l
     p.right = g.right;
     p.prefix = mask->prefix < Nk ? mask->prefix : Nk;
     p.kv_len = mask->kv_len;
+    p.anchor = mask->diag_from_kv_len;
     const int grid = p.per_xcd * 8;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
@@ -587,6 +590,7 @@ int fa_decode_masked(const void *q, const void *k, const void *v, void *o, float
     p.right = g.right;
     p.prefix = mask->prefix < Nk ? mask->prefix : Nk;
     p.kv_len = mask->kv_len;
+    p.anchor = mask->diag_from_kv_len;
     p.nsplit = pl.nsplit;
     p.part_o = (float *)workspace;
     p.part_ml = p.part_o + (size_t)pl.nsplit * heads * D;

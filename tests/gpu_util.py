@@ -53,7 +53,8 @@ def run_fa_fwd_splitkv(q_bits, k_bits, v_bits, scale, causal, dtype, nsplit=0, e
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy(), plan
 
 
-def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None):
+def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None,
+                      diag_from_kv_len=0):
     """Same as run_fa_fwd through fa_fwd_masked; kv_len (list of B ints or None) is copied to the GPU."""
     import torch
     assert torch.cuda.is_available()
@@ -67,12 +68,14 @@ def run_fa_fwd_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, p
     tl = torch.full((B, H, Nq), float("nan"), dtype=torch.float32, device=dev)
     tlen = None if kv_len is None else torch.tensor(list(kv_len), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
-    fa.fa_fwd_masked(tq, tk, tv, to, tl, B, H, Nq, Nk, D, scale, left, right, prefix, tlen, dtype, stream)
+    fa.fa_fwd_masked(tq, tk, tv, to, tl, B, H, Nq, Nk, D, scale, left, right, prefix, tlen, dtype, stream,
+                     diag_from_kv_len)
     torch.cuda.synchronize()
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy()
 
 
-def run_fa_decode_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None, nsplit=0):
+def run_fa_decode_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1, prefix=0, kv_len=None, nsplit=0,
+                         diag_from_kv_len=0):
     """One decoding step through fa_decode_masked (q_bits [B,H,1,D]); the workspace is filled with NaN first.
     Returns (o_bits, lse, plan)."""
     import torch
@@ -91,7 +94,7 @@ def run_fa_decode_masked(q_bits, k_bits, v_bits, scale, dtype, left=-1, right=-1
     ws = torch.full(((plan.workspace_bytes + 3) // 4 + 4,), float("nan"), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     fa.fa_decode_masked(tq, tk, tv, to, tl, B, H, Nk, D, scale, left, right, prefix, tlen, dtype, nsplit, ws,
-                        plan.workspace_bytes, stream)
+                        plan.workspace_bytes, stream, diag_from_kv_len)
     torch.cuda.synchronize()
     return to.cpu().numpy().view(np.uint16), tl.cpu().numpy(), plan
 

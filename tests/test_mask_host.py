@@ -16,11 +16,11 @@ def lib():
     return fa.load()
 
 
-def keep_matrix(Nq, Nk, left, right, prefix, klen):
-    """The predicate of include/fa.h, written out per element."""
+def keep_matrix(Nq, Nk, left, right, prefix, klen, anchor=0):
+    """The predicate of include/fa.h, written out per element (anchor: the diag_from_kv_len member)."""
     i = np.arange(Nq)[:, None]
     j = np.arange(Nk)[None, :]
-    diag = i + (Nk - Nq)
+    diag = i + ((klen if anchor else Nk) - Nq)
     win = np.ones((Nq, Nk), dtype=bool)
     if left >= 0:
         win &= j >= diag - left
@@ -37,16 +37,17 @@ DESCRIPTORS = [
 SHAPES = [(300, 300), (130, 700), (700, 130), (1, 500), (257, 64), (64, 65)]
 
 
+@pytest.mark.parametrize("anchor", [0, 1])
 @pytest.mark.parametrize("Nq,Nk", SHAPES)
 @pytest.mark.parametrize("left,right,prefix", DESCRIPTORS)
-def test_tile_class_is_never_wrong_and_exact_where_it_must_be(lib, left, right, prefix, Nq, Nk):
+def test_tile_class_is_never_wrong_and_exact_where_it_must_be(lib, left, right, prefix, Nq, Nk, anchor):
     for klen in sorted({Nk, max(Nk - 37, 0), min(64, Nk), 0}):
-        keep = keep_matrix(Nq, Nk, left, right, prefix, klen)
+        keep = keep_matrix(Nq, Nk, left, right, prefix, klen, anchor)
         for r0 in range(0, Nq, 32):                       # a wave's 32 rows
             r1 = min(r0 + 31, Nq - 1)
             for k0 in range(0, Nk, BN):
                 blk = keep[r0:r1 + 1, k0:k0 + BN]
-                cls = fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, k0)
+                cls = fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, k0, anchor)
                 if cls == fa.FA_TILE_SKIP:
                     assert not blk.any(), (r0, k0, klen)
                 elif cls == fa.FA_TILE_FULL:
@@ -60,15 +61,16 @@ def test_tile_class_is_never_wrong_and_exact_where_it_must_be(lib, left, right, 
                     assert cls == want, (r0, k0, klen, cls, want)
 
 
+@pytest.mark.parametrize("anchor", [0, 1])
 @pytest.mark.parametrize("Nq,Nk", SHAPES)
 @pytest.mark.parametrize("left,right,prefix", DESCRIPTORS)
-def test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk):
+def test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk, anchor):
     ntiles = (Nk + BN - 1) // BN
-    for klen in sorted({Nk, max(Nk - 37, 0), 0}):
-        keep = keep_matrix(Nq, Nk, left, right, prefix, klen)
+    for klen in sorted({Nk, max(Nk - 37, 0), Nk // 2, 0}):
+        keep = keep_matrix(Nq, Nk, left, right, prefix, klen, anchor)
         for R0 in range(0, Nq, 256):                      # a workgroup's 256 rows
             R1 = min(R0 + 255, Nq - 1)
-            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1)
+            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1, anchor)
             assert len(set(walk)) == len(walk) and all(0 <= t < ntiles for t in walk)
             assert all(t * BN < klen for t in walk)       # never a tile of pure padding
             needed = {t for t in range(ntiles) if keep[R0:R1 + 1, t * BN:(t + 1) * BN].any()}
@@ -84,19 +86,20 @@ def test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left
                     assert all(t % len(walk) == i for i, t in enumerate(walk))
 
 
+@pytest.mark.parametrize("anchor", [0, 1])
 @pytest.mark.parametrize("Nq,Nk", SHAPES + [(1024, 1024), (300, 1100)])
 @pytest.mark.parametrize("left,right,prefix", DESCRIPTORS + [(300, 0, 0), (400, 100, 0), (-1, 0, 300), (500, 0, 256)])
-def test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk):
-    for klen in sorted({Nk, max(Nk - 37, 0), 0}):
+def test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk, anchor):
+    for klen in sorted({Nk, max(Nk - 37, 0), Nk // 2, 0}):
         for R0 in range(0, Nq, 256):
             R1 = min(R0 + 255, Nq - 1)
-            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1)
+            walk = fa.fa_mask_tile_walk(left, right, prefix, klen, Nq, Nk, R0, R1, anchor)
             for r0 in range(R0, R1 + 1, 32):
                 r1 = min(r0 + 31, Nq - 1)
-                first, count = fa.fa_mask_interior_run(left, right, prefix, klen, Nq, Nk, R0, R1, r0, r1)
+                first, count = fa.fa_mask_interior_run(left, right, prefix, klen, Nq, Nk, R0, R1, r0, r1, anchor)
                 assert first % 2 == 0 and count % 2 == 0 and first >= 0 and count >= 0
                 assert first + count <= max(len(walk) - 1, 0)        # a next position always exists
-                cls = [fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, t * BN) for t in walk]
+                cls = [fa.fa_mask_tile_class(left, right, prefix, klen, Nq, Nk, r0, r1, t * BN, anchor) for t in walk]
                 for j in range(first, first + count):
                     assert cls[j] == fa.FA_TILE_FULL, (klen, R0, r0, j)
                     assert (walk[j + 1] + 1) * BN <= Nk, (klen, R0, r0, j)   # loaded without a bounds check
@@ -120,8 +123,9 @@ BIG_DESCRIPTORS = [(2200, 0, 0), (2048, 300, 0), (2300, 0, 128), (2100, 2100, 0)
 @pytest.mark.parametrize("left,right,prefix", BIG_DESCRIPTORS)
 def test_long_windows_are_walked_rotated_and_still_cover_everything(lib, left, right, prefix, Nq, Nk):
     """Window runs of 32 tiles and more: the rotated walk, its classification and its check-free run."""
-    test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk)
-    test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk)
+    for anchor in (0, 1):
+        test_tile_walk_covers_every_visible_tile_once_and_nothing_far_away(lib, left, right, prefix, Nq, Nk, anchor)
+        test_interior_run_only_holds_tiles_that_need_no_check(lib, left, right, prefix, Nq, Nk, anchor)
     rotated = 0
     for R0 in range(0, Nq, 256):
         R1 = min(R0 + 255, Nq - 1)
@@ -208,12 +212,14 @@ def test_null_descriptor_and_bad_host_queries(lib):
     with pytest.raises(fa.FaError):
         fa.fa_mask_tile_walk(-1, 0, -2, 8, 8, 8, 0, 7)
     import ctypes
-    m = fa.FaMask(-1, 0, 0, None)
+    bad = fa.FaMask(-1, 0, 0, 2, None)                            # the diagonal flag is 0 or 1
+    assert fa.load().fa_mask_tile_class(ctypes.byref(bad), 8, 8, 8, 0, 7, 0) == fa.FA_ERR_MASK
+    m = fa.FaMask(-1, 0, 0, 0, None)
     tiles, n = (ctypes.c_int * 4)(), ctypes.c_int()
     assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, tiles, 4, None) == fa.FA_ERR_NULL
     assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, None, 4, ctypes.byref(n)) == fa.FA_ERR_NULL
     assert fa.load().fa_mask_tile_walk(ctypes.byref(m), 8, 8, 8, 0, 7, tiles, -1, ctypes.byref(n)) == fa.FA_ERR_SHAPE
     # a short array gets the first tiles only; the count is the whole walk's
-    m2 = fa.FaMask(-1, 0, 0, None)
+    m2 = fa.FaMask(-1, 0, 0, 0, None)
     assert fa.load().fa_mask_tile_walk(ctypes.byref(m2), 640, 640, 640, 384, 639, tiles, 4, ctypes.byref(n)) == fa.FA_OK
     assert n.value == 10 and list(tiles) == [0, 1, 2, 3]

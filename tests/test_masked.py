@@ -160,3 +160,60 @@ def test_decode_masked_in_shares(oracle, mask, dtype, nsplit):
         o, lse, plan = run_fa_decode_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, nsplit)
         assert plan.nsplit >= 1 and (nsplit == 0 or plan.nsplit == min(nsplit, (Nk + 63) // 64))
         check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"decode masked shares D={D} {mask} nsplit={nsplit}")
+
+
+OWN_DIAGONAL_MASKS = [
+    # left, right, prefix, per-batch key counts as fractions of Nk
+    (-1, 0, 0, (1.0, 0.37, 0.0)), (99, 0, 0, (0.9, 0.5, 0.02)), (500, 0, 0, (1.0, 0.1, 0.6)), (0, 0, 0, (0.5, 1.0, 0.001)),
+    (300, 0, 64, (0.7, 0.05, 0.3)), (200, 5, 0, (1.0, 0.999, 0.6)),
+]
+
+
+@pytest.mark.parametrize("kernel", ["stream", "mfma"])
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", OWN_DIAGONAL_MASKS)
+def test_decoding_step_with_the_diagonal_at_each_caches_own_last_key(oracle, mask, dtype, kernel):
+    """diag_from_kv_len = 1 (include/fa.h): a batch of caches of different lengths in Nk allocated rows, the new
+    token's query sitting on the last key of ITS cache, so that a sliding window covers the last W keys of each
+    cache (without the flag it hangs on key Nk - 1 and misses the short caches).  Through fa_fwd_masked (both
+    kernels) and through fa_decode_masked in shares."""
+    options.set_decode(kernel)
+    left, right, prefix, frac = mask
+    B, H, Nk = 3, 2, 3001
+    for D in (64, 128):
+        kv_len = [int(round(f * Nk)) for f in frac]
+        print(f"case own diagonal decode D={D} mask=({left},{right},{prefix},{kv_len}) dtype={dtype} kernel={kernel}", flush=True)
+        rng = np.random.default_rng(hash((mask[:3], dtype, D, 21)) % (2**32))
+        q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (1, Nk, Nk))
+        scale = 1.0 / math.sqrt(D)
+        o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len,
+                                                     diag_from_kv_len=True)
+        # the case is what it claims to be: short caches are seen (not -inf as they would be without the flag)
+        assert np.isfinite(lse_ref[[i for i, n in enumerate(kv_len) if n > 0]]).all()
+        o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=1)
+        check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"own diagonal decode D={D} {mask}")
+        if kernel == "stream":
+            for nsplit in (0, 3):
+                o, lse, _ = run_fa_decode_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, nsplit, diag_from_kv_len=1)
+                check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"own diagonal shares D={D} {mask} nsplit={nsplit}")
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("mask", [(-1, 0, 0), (100, 0, 0), (63, 0, 40), (300, 20, 0), (-1, -1, 0)])
+@pytest.mark.parametrize("shape", [(3, 2, 130, 700, 64), (3, 1, 300, 1000, 128), (3, 1, 520, 777, 128), (3, 2, 300, 300, 64)])
+def test_chunk_of_queries_with_the_diagonal_at_each_caches_own_last_key(oracle, shape, mask, dtype):
+    """The same flag for Nq > 1 (a chunk of a chunked prefill over caches of different lengths): the Nq queries are
+    the last Nq positions of each entry's own keys; an entry with fewer keys than queries leaves its first rows
+    without any visible key (o = 0, lse = -inf) unless a prefix covers them."""
+    B, H, Nq, Nk, D = shape
+    left, right, prefix = mask
+    kv_len = [Nk, int(0.55 * Nk), min(Nq // 2, Nk)]
+    print(f"case own diagonal chunk shape={shape} mask={mask} kv_len={kv_len} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, mask, dtype, 22)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=True)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=1)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"own diagonal chunk {shape} {mask} dt={dtype}")
+    empty = np.isneginf(lse_ref)
+    assert (I.bits_to_f64(o, dtype)[empty] == 0).all()

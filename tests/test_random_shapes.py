@@ -87,11 +87,12 @@ def test_fa_fwd_masked_random(oracle, case):
     prefix = 0 if rng.random() < 0.5 else int(rng.integers(1, Nk + 50))
     kv_len = None if rng.random() < 0.5 else [int(rng.integers(0, Nk + 1)) for _ in range(B)]
     label = (f"masked case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} scale={scale:.3f} "
-             f"mask=({left},{right},{prefix},{kv_len})")
+             f"mask=({left},{right},{prefix},{kv_len}) own_diagonal={int(kv_len is not None and case % 3 == 0)}")
     print("case " + label, flush=True)
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
-    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
-    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+    own = int(kv_len is not None and case % 3 == 0)      # the diagonal at each entry's own last key
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=own)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=own)
     check_against_oracle(o, lse, o_ref, lse_ref, dtype, label)
 
 
@@ -178,8 +179,10 @@ def test_fa_fwd_masked_random_medium(oracle, case):
     print("case " + label, flush=True)
     q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
     ids, b, h, i = sample(rng, B, H, Nq)
-    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, rows=ids)
-    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len)
+    own = int(kv_len is not None and case % 2 == 0)
+    o_ref, lse_ref = oracle.attention_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, rows=ids,
+                                                 diag_from_kv_len=own)
+    o, lse = run_fa_fwd_masked(q, k, v, scale, dtype, left, right, prefix, kv_len, diag_from_kv_len=own)
     check_against_oracle(o[b, h, i], lse[b, h, i], o_ref, lse_ref, dtype, label)
 
 
