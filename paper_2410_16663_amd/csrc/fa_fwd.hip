@@ -862,7 +862,7 @@ const char *fa_strerror(int code) {
     }
 }
 
-int fa_version(void) { return 200; }
+int fa_version(void) { return 300; }
 
 int fa_last_hip_error(void) { return g_last_hip_error; }
 
