@@ -479,7 +479,8 @@ def oracle_leg(cfg, host, outputs, np, I, time_it):
     return parity, cpu
 
 
-KERNEL_OF_MODE = {0: "split", 1: "wide", 2: "wide, folded rows", 3: "streaming decode"}
+KERNEL_OF_MODE = {0: "fa_fwd_kernel (split)", 1: "fa_fwd_kernel (wide)", 2: "fa_fwd_kernel (wide, folded rows)",
+                  3: "fa_decode_kernel (streaming decode)", 4: "fa_fwd_wide64_kernel (64-row waves, pipelined loop)"}
 
 
 def roofline_entry(cfg, event_ms, plan):
@@ -487,7 +488,7 @@ def roofline_entry(cfg, event_ms, plan):
     achieved = flops / (event_ms * 1e-3) / 1e12
     return {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), **traffic_fields(cfg.name),
-            "kernel": "fa_fwd_kernel (%s)" % KERNEL_OF_MODE[plan.mode], "avg_launch_ms": round(event_ms, 5),
+            "kernel": KERNEL_OF_MODE[plan.mode], "avg_launch_ms": round(event_ms, 5),
             "flops_per_launch": flops,
             "timing": "HIP events on the launch stream around the timed steps"}
 
@@ -514,7 +515,7 @@ def main():
                     help="time only the sliding-window workload at head dimension 64 (for profiling runs)")
     ap.add_argument("--decode-only", action="store_true",
                     help="time only the decoding workload through fa_fwd_splitkv (for profiling runs)")
-    ap.add_argument("--fwd-mode", default=None, choices=["split", "wide", "fold"],
+    ap.add_argument("--fwd-mode", default=None, choices=["split", "wide", "fold", "wide64"],
                     help="force fa_fwd's work decomposition (fa_set_option; for profiling and tuning runs)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle (baseline and parity)")
@@ -548,7 +549,7 @@ def main():
 
     if args.fwd_mode:
         fa.fa_set_option(fa.FA_OPT_FWD_MODE, {"split": fa.FA_MODE_SPLIT, "wide": fa.FA_MODE_WIDE,
-                                              "fold": fa.FA_MODE_WIDE_FOLD}[args.fwd_mode])
+                                              "fold": fa.FA_MODE_WIDE_FOLD, "wide64": fa.FA_MODE_WIDE64}[args.fwd_mode])
     if args.no_linear_overlap:
         fa.fa_set_option(fa.FA_OPT_LINEAR_OVERLAP, 0)
     cfg = I.CONFIGS[args.workload]

@@ -76,9 +76,14 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * tiles; FA_MODE_WIDE_FOLD (causal only): WIDE with each workgroup's eight 32-row blocks taken
  * four from the cheap end of the sequence and four, mirrored, from the expensive end; once the
  * cheap blocks are done their waves take every other tile of the expensive ones.
+ * FA_MODE_WIDE64 (D = 128 only): 256 query rows per workgroup as in WIDE, but as four waves of 64
+ * rows, one per SIMD, so that every K and V fragment read from LDS feeds two matrix instructions,
+ * with a software-pipelined main loop (the softmax of one 32-key unit issued between the matrix
+ * instructions of its neighbours).
  * With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256; for causal problems with
  * Nq > 768: WIDE_FOLD when Nq <= 4096, W <= 1024 and the last round of 256 workgroups is at
- * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); WIDE otherwise.
+ * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); otherwise WIDE64 when
+ * D = 128 and Nq >= 8192, else WIDE.
  * fa_set_option(FA_OPT_FWD_MODE, ...) overrides the choice (tests, tuning).
  * Nq = 1 (one decoding step) takes none of these: FA_MODE_STREAM, the register-streaming kernel
  * described at fa_fwd_splitkv, one workgroup per (batch, head) -- full speed when B*H fills the
@@ -89,9 +94,10 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
 #define FA_MODE_WIDE  1
 #define FA_MODE_WIDE_FOLD 2
 #define FA_MODE_STREAM 3   /* Nq = 1: the register-streaming kernel of fa_fwd_splitkv, one run per (batch, head) */
+#define FA_MODE_WIDE64 4   /* D = 128: four waves of 64 rows, software-pipelined main loop */
 
 typedef struct fa_plan {
-    int mode;                 /* FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD or FA_MODE_STREAM */
+    int mode;                 /* FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD, FA_MODE_STREAM or FA_MODE_WIDE64 */
     int block_m;              /* query rows per workgroup */
     int block_n;              /* keys per tile */
     int threads;              /* threads per workgroup */
@@ -333,7 +339,7 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
  * environment variable is read anywhere in the library.
  *
  *   FA_OPT_FWD_MODE      : FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD (causal problems only; WIDE
- *                          otherwise) or FA_AUTO
+ *                          otherwise), FA_MODE_WIDE64 (D = 128 only; WIDE otherwise) or FA_AUTO
  *   FA_OPT_DECODE_KERNEL : 0 or FA_AUTO: Nq = 1 runs the register-streaming kernel; 1: the tile kernels
  *   FA_OPT_LINEAR_TILE   : 128, 256 or FA_AUTO: token rows per workgroup tile of the projection
  *   FA_OPT_LINEAR_PANEL  : >= 1 or FA_AUTO: row tiles per panel of the projection's tile order

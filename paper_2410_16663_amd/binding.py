@@ -37,6 +37,7 @@ FA_DTYPE_F16 = 0
 FA_DTYPE_BF16 = 1
 FA_MODE_SPLIT = 0
 FA_MODE_WIDE = 1
+FA_MODE_WIDE64 = 4
 FA_MODE_WIDE_FOLD = 2
 FA_MODE_STREAM = 3
 

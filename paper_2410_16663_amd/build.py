@@ -14,8 +14,10 @@ SRC = os.path.join(HERE, "csrc", "fa_fwd.hip")
 HDR = os.path.join(os.path.dirname(HERE), "include", "fa.h")
 # fragments of the one translation unit, included by fa_fwd.hip
 FRAGMENTS = [os.path.join(HERE, "csrc", n) for n in (
-    "fa_types.inc", "fa_mask.inc", "fa_device.inc", "fa_attention_kernel.inc", "fa_linear_kernel.inc",
-    "fa_decode_kernels.inc")]
+    "fa_types.inc", "fa_mask.inc", "fa_device.inc", "fa_attention_kernel.inc", "fa_attention_wide64_kernel.inc",
+    "fa_linear_kernel.inc", "fa_decode_kernels.inc", "gen_fa_wide64_loop.py")]
+# written by gen_fa_wide64_loop.py at build time (hand-scheduled assembly of a regular loop: generated, not typed)
+GENERATED = os.path.join(HERE, "csrc", "fa_attention_wide64_loop.inc")
 LIB = os.path.join(HERE, "libfa.so")
 
 HIPCC_FLAGS = [
@@ -36,6 +38,15 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     return any(os.path.getmtime(f) > t for f in [SRC, HDR] + FRAGMENTS)
+
+
+def generate_fragments() -> None:
+    """Run the generator of the wide64 kernel's main loop (the compile includes its output)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("gen_fa_wide64_loop", os.path.join(HERE, "csrc", "gen_fa_wide64_loop.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.generate(GENERATED)
 
 
 def parse_resource_report(stderr: str) -> dict:
@@ -62,6 +73,8 @@ def check_resource_report(report: dict) -> None:
         bad = {k: v for k, v in r.items() if k in ("ScratchSize [bytes/lane]", "VGPRs Spill") and v}
         if bad:
             raise RuntimeError(f"kernel {name} uses scratch memory: {bad}")
+        if "fa_fwd_wide64_kernel" in name:
+            continue        # one wave per SIMD by design: the whole register file
         if r.get("VGPRs", 0) + r.get("AGPRs", 0) > 256:
             raise RuntimeError(f"kernel {name} needs more than 256 registers: two waves per SIMD no longer fit")
 
@@ -70,6 +83,7 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
     """Compile libfa.so. ``force=False`` skips the compile when the library is newer than its sources."""
     if not force and not is_stale():
         return LIB
+    generate_fragments()
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + list(extra) + [SRC, "-o", LIB]
     if verbose:

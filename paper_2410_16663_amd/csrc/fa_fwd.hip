@@ -64,6 +64,7 @@ namespace {
 #include "fa_mask.inc"
 #include "fa_device.inc"
 #include "fa_attention_kernel.inc"
+#include "fa_attention_wide64_kernel.inc"
 #include "fa_linear_kernel.inc"
 #include "fa_decode_kernels.inc"
 
@@ -151,6 +152,7 @@ bool use_streaming_decode(int Nq) { return Nq == 1 && option(FA_OPT_DECODE_KERNE
 int choose_mode(int B, int H, int Nq, int D, int causal) {
     const int forced = option(FA_OPT_FWD_MODE);
     if (forced == FA_MODE_SPLIT || forced == FA_MODE_WIDE) return forced;
+    if (forced == FA_MODE_WIDE64) return D == 128 ? FA_MODE_WIDE64 : FA_MODE_WIDE;
     if (forced == FA_MODE_WIDE_FOLD) return causal ? FA_MODE_WIDE_FOLD : FA_MODE_WIDE;
     const long long nqt = ((long long)Nq + 255) / 256;
     const long long W = (long long)B * H * nqt;
@@ -161,6 +163,9 @@ int choose_mode(int B, int H, int Nq, int D, int causal) {
         if (Nq <= 4096 && W <= 1024 && fills_last_round) return FA_MODE_WIDE_FOLD;
         if (Nq <= 4096 ? W < 640 : W < 384) return FA_MODE_SPLIT;
     }
+    // long walks at D = 128: the 64-row waves with the pipelined loop (the loop takes whole unmasked tiles two at
+    // a time, so it needs walks long enough to consist mostly of those)
+    if (D == 128 && Nq >= 8192) return FA_MODE_WIDE64;
     return FA_MODE_WIDE;
 }
 
@@ -220,6 +225,14 @@ hipError_t launch_pair(const FaParams &p, int nwork_padded, hipStream_t stream) 
 // the plain instantiations: (split | wide) x dtype x head dimension x causal, and the paired fold (causal only)
 hipError_t launch_attention(const FaParams &p, int mode, int D, int causal, int dtype, int grid, hipStream_t st) {
     hipError_t e;
+    if (mode == FA_MODE_WIDE64) {
+        if (D != 128) return hipErrorInvalidValue;
+        if (dtype == 0 && causal) hipLaunchKernelGGL((fa_fwd_wide64_kernel<0, true>), dim3(grid), dim3(256), 0, st, p);
+        else if (dtype == 0) hipLaunchKernelGGL((fa_fwd_wide64_kernel<0, false>), dim3(grid), dim3(256), 0, st, p);
+        else if (causal) hipLaunchKernelGGL((fa_fwd_wide64_kernel<1, true>), dim3(grid), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((fa_fwd_wide64_kernel<1, false>), dim3(grid), dim3(256), 0, st, p);
+        return hipGetLastError();
+    }
     if (mode == FA_MODE_WIDE_FOLD && causal) {
         switch ((dtype << 1) | (D == 128)) {
             case 0: return launch_pair<0, 64>(p, grid, st);
@@ -348,12 +361,13 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
     plan->mode = mode;
     plan->block_m = BM;
     plan->block_n = BN;
-    plan->threads = 512;
+    plan->threads = mode == FA_MODE_WIDE64 ? 256 : 512;
     plan->grid = (int)(((nwork + 7) / 8) * 8);
     plan->work_items = nwork;
     plan->tiles_visited = visited * B * H;
     plan->tiles_total = nwork * tiles_k;
     plan->lds_bytes = (mode == FA_MODE_WIDE ? 1 : 2) * 4 * BN * D * 2;    // sets of 2+2 tiles
+    if (mode == FA_MODE_WIDE64) plan->lds_bytes = 4 * (16 * 1088 + BN * D * 2);   // ring of four (padded K tile, V tile)
     return FA_OK;
 }
 
@@ -831,7 +845,9 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
 int fa_set_option(int opt, int value) {
     bool ok = value == FA_AUTO;
     switch (opt) {
-        case FA_OPT_FWD_MODE: ok = ok || value == FA_MODE_SPLIT || value == FA_MODE_WIDE || value == FA_MODE_WIDE_FOLD; break;
+        case FA_OPT_FWD_MODE:
+            ok = ok || value == FA_MODE_SPLIT || value == FA_MODE_WIDE || value == FA_MODE_WIDE_FOLD || value == FA_MODE_WIDE64;
+            break;
         case FA_OPT_DECODE_KERNEL: ok = ok || value == 0 || value == 1; break;
         case FA_OPT_LINEAR_TILE: ok = ok || value == 128 || value == 256; break;
         case FA_OPT_LINEAR_PANEL: ok = ok || value >= 1; break;

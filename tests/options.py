@@ -2,12 +2,13 @@
 tests/conftest.py puts every option back to automatic after each test."""
 from paper_2410_16663_amd import binding as fa
 
-_FWD = {"split": fa.FA_MODE_SPLIT, "wide": fa.FA_MODE_WIDE, "fold": fa.FA_MODE_WIDE_FOLD, None: fa.FA_AUTO}
+_FWD = {"split": fa.FA_MODE_SPLIT, "wide": fa.FA_MODE_WIDE, "fold": fa.FA_MODE_WIDE_FOLD, "wide64": fa.FA_MODE_WIDE64,
+        None: fa.FA_AUTO}
 _DEC = {"stream": 0, "mfma": 1, None: fa.FA_AUTO}
 
 
 def set_fwd_mode(name):
-    """"split" | "wide" | "fold" | None (automatic)"""
+    """"split" | "wide" | "fold" | "wide64" | None (automatic)"""
     fa.fa_set_option(fa.FA_OPT_FWD_MODE, _FWD[name])
 
 

@@ -66,7 +66,7 @@ def test_whole_problem_in_blocks(oracle, shape, rows_per_block, causal, dtype):
     check_y(y, y_ref, f"{shape} rpb={rows_per_block}")
 
 
-@pytest.mark.parametrize("mode", ["split", "wide", "fold"])
+@pytest.mark.parametrize("mode", ["split", "wide", "fold", "wide64"])
 def test_blocks_are_independent_and_touch_only_their_rows(oracle, monkeypatch, mode):
     """Arbitrary blocks, out of order, leaving a gap: the gap's rows of o, lse, y stay as they were.  Every
     decomposition of the attention launch is run on a block whose first row is not row 0."""

@@ -28,7 +28,7 @@ SHAPES = [
 ]
 
 
-@pytest.fixture(params=["split", "wide", "fold"])
+@pytest.fixture(params=["split", "wide", "fold", "wide64"])
 def mode(request, monkeypatch):
     """Force each work decomposition in turn (FA_OPT_FWD_MODE of include/fa.h)."""
     options.set_fwd_mode(request.param)
@@ -66,6 +66,55 @@ def test_folded_mode_on_longer_causal_shapes(oracle, monkeypatch, shape, dtype):
     o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, True, dtype)
     o, lse = run_fa_fwd(q, k, v, scale, True, dtype)
     check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"fold {shape} dt={dtype}")
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shape", [(1, 2, 2048, 2048, 128), (1, 1, 4096, 4096, 128), (1, 2, 1000, 1300, 128),
+                                   (1, 1, 1300, 1000, 128), (2, 1, 1025, 3000, 128), (1, 2, 300, 5000, 128)])
+def test_wide64_mode_on_longer_shapes(oracle, shape, causal, dtype):
+    """FA_MODE_WIDE64 on walks long enough for its pipelined loop (which takes whole unmasked tiles two at a
+    time and leaves the rest to the general loop): several workgroups per head, ragged ends, more keys than
+    queries and fewer, waves whose second 32-row block is partly or wholly past the last query."""
+    options.set_fwd_mode("wide64")
+    B, H, Nq, Nk, D = shape
+    print(f"case wide64 shape={shape} causal={causal} dtype={dtype}", flush=True)
+    assert fa.fa_fwd_plan(B, H, Nq, Nk, D, int(causal), dtype).mode == fa.FA_MODE_WIDE64
+    rng = np.random.default_rng(hash((shape, causal, dtype, 64)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
+    o, lse = run_fa_fwd(q, k, v, scale, causal, dtype)
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"wide64 {shape} causal={causal} dt={dtype}")
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("pattern", ["rising", "late_spike", "staircase"])
+def test_wide64_reference_moves_inside_the_pipelined_loop(oracle, pattern, dtype):
+    """Row maxima that keep rising over a long walk of unmasked tiles: inside FA_MODE_WIDE64's pipelined loop the
+    reference moves through a block out of line that recomputes the unit's logits and rescales accumulators that
+    live in the accumulation registers -- here with non-zero accumulators, in both row blocks of a wave, many times."""
+    options.set_fwd_mode("wide64")
+    print(f"case wide64 moving maximum pattern={pattern} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(82)
+    D, Nq, Nk = 128, 320, 2048
+    qf = rng.standard_normal((1, 2, Nq, D), dtype=np.float32)
+    kf = rng.standard_normal((1, 2, Nk, D), dtype=np.float32) * np.float32(0.05)
+    vf = rng.standard_normal((1, 2, Nk, D), dtype=np.float32)
+    u = qf.mean(axis=2, keepdims=True)
+    u /= np.linalg.norm(u, axis=-1, keepdims=True)
+    qf = qf * np.float32(0.2) + 6.0 * u
+    j = np.arange(Nk, dtype=np.float32)
+    amp = {"rising": j / 64.0, "late_spike": np.where(j == Nk - 300, 25.0, 0.0),
+           "staircase": np.floor(j / 256.0) * 5.0}[pattern].astype(np.float32)
+    kf = kf + amp[None, None, :, None] * u
+    q, k, v = (I.f32_to_bits(a, dtype) for a in (qf, kf, vf))
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, 1.0, False, dtype)
+    o, lse = run_fa_fwd(q, k, v, 1.0, False, dtype)
+    of = I.bits_to_f64(o, dtype)
+    assert np.isfinite(of).all() and np.isfinite(lse).all()
+    assert np.abs(of - o_ref).max() <= (1e-2 if dtype == I.F16 else 2e-2)
+    assert (np.abs(lse - lse_ref) <= 1e-3 + 1e-6 * np.abs(lse_ref)).all()
 
 
 @pytest.mark.parametrize("scale", [-0.2, 0.0, 1.0, 1e-3])

@@ -45,7 +45,7 @@ def test_fa_fwd_random(oracle, monkeypatch, case):
     rng = np.random.default_rng(7000 + case)
     B, H, Nq, Nk, D, dtype, scale = draw_problem(rng)
     causal = bool(rng.integers(0, 2))
-    mode = str(rng.choice(["auto", "split", "wide", "fold"]))
+    mode = str(rng.choice(["auto", "split", "wide", "fold", "wide64"]))
     if mode != "auto":
         options.set_fwd_mode(mode)
     label = f"fa_fwd case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} scale={scale:.3f} causal={causal} mode={mode}"
@@ -151,7 +151,7 @@ def test_fa_fwd_random_medium(oracle, monkeypatch, case):
     rng = np.random.default_rng(11000 + case)
     B, H, Nq, Nk, D, dtype, scale = draw_medium(rng)
     causal = rng.random() < 0.7
-    mode = str(rng.choice(["auto", "split", "wide", "fold"]))
+    mode = str(rng.choice(["auto", "split", "wide", "fold", "wide64"]))
     if mode != "auto":
         options.set_fwd_mode(mode)
     label = f"fa_fwd medium case={case} B={B} H={H} Nq={Nq} Nk={Nk} D={D} dt={dtype} causal={causal} mode={mode}"
