@@ -1,23 +1,53 @@
 #!/usr/bin/env python3
-"""Writes fa_attention_wide64_loop.inc: the software-pipelined check-free main loop for waves of 64 query rows
-(two 32-row blocks rb = 0, 1 that share every K and V fragment read from LDS).  One wave per SIMD, 512 registers.
+"""Writes fa_attention_wide64_loop.inc: the check-free main loop of fa_fwd_wide64_kernel as one inline-assembly
+block per storage type -- the software-pipelined form of the attention loop for waves of 64 query rows (two 32-row
+blocks rb = 0, 1 that share every K and V fragment read from LDS).  One wave per SIMD, the whole register file.
+
+Why assembly, and why generated: with one wave per SIMD nothing hides a wave's vector work but the wave itself, so
+the instruction stream has to alternate -- one matrix instruction, then about as many vector / LDS / load
+instructions as issue while it runs, then the next -- with three pieces of work in flight that do not depend on
+each other.  The compiler's scheduler undoes such an interleaving and the rotating buffers confuse its register
+allocator, hence fixed registers and a fixed order; the loop is regular, hence written by a script.  The build runs
+this script (paper_2410_16663_amd/build.py); the .inc file is its output and is not kept under version control.
 
 Register plan (per lane):
     a0   .. a127   O accumulators, O[rb][db] = a[64*rb + 16*db : +15]        (outputs of the block)
     a128 .. a191   Q fragments,    Q[rb][kb] = a[128 + 32*rb + 4*kb : +3]    (inputs)
-    v0   .. v127   four unit buffers x two row blocks, X[b][rb] = v[32*b + 16*rb : +15]
+    v0   .. v127   four unit buffers x two row blocks, X[b][rb] = v[32*b + 16*rb : +15]: unit u lives in X[u % 4],
+                   first as logits, then (overwritten in place) as packed exponentials P[jj] = first 4 registers of
+                   each half
     v128 .. v143   four K fragments in flight;   v144 .. v159   four V^T fragments in flight
     v160+rb m_ref, v162+rb l_run, v164+rb l_rnd                               (outputs)
     v166, v167     K fragment address, even (input) / odd k-step
     v168 .. v171   V^T fragment address per 32-row block of O^T (v168 input)
     v172, v173     per-lane byte offsets of the K and V loads from global memory (inputs)
-    v174 .. v185   temporaries, six per row block
+    v174 .. v185   temporaries, six per row block;   v186 .. v193   per-lane offsets of the four loads per tensor
 Scalar registers s60 .. s69 are scratch of the block.
 
-A unit is 32 keys x the wave's 64 rows.  In step u the wave issues the 16 matrix instructions of unit u+1's logits,
-the 16 of unit u-1's second product, and between them the vector instructions of unit u's softmax (both row
-blocks).  LDS ring, barriers and loads as in the 32-row pipelined loop, with four waves sharing the loads (four
-instructions per wave, tensor and tile).
+A UNIT is 32 keys x the wave's 64 rows.  In step u the wave issues
+    the 16 matrix instructions of unit u+1's logits   S(u+1) = K Q^T,
+    the 16 matrix instructions of unit u-1's second product   O += V^T P(u-1),
+    and BETWEEN them the ~150 vector instructions of unit u's softmax   S(u) -> P(u)   (both row blocks), the
+    LDS reads of the fragments three matrix-instruction pairs ahead, and this wave's share of a tile's loads,
+each matrix instruction followed by at most CAP cycles' worth of the others (by a simple cost table; the best CAP
+was found by timing).  The test "row sum <= 256" (which proves that no exponential exceeded 256, see the kernel)
+is computed at the end of the step's vector work and branched on after its last matrix instruction; the rare other
+case runs a block out of line that recomputes the unit's logits, takes the row maxima, moves the references,
+rescales the accumulators (through v_accvgpr_read / write) and redoes the exponentials.
+
+LDS: four stages of (K tile, V tile); tile t lives in stage t % 4.  Barrier k (the k-th of the walk, the same count
+as in the compiler-scheduled loop around this block) publishes tile k+1 and certifies that no wave reads tile k-1
+any more; between barrier k and barrier k+1 every wave issues its share (four loads per tensor) of tile k+3.
+
+Steps: the block computes S(0), runs step 0 (no second product yet), then the steady loop -- eight steps per pass,
+so that buffers and stages come round to where they started -- and leaves after step 2J-1 (J = number of tiles, even)
+through one of two exits, each followed by the second product of the last unit.
+
+Hazards the hardware does not interlock, spaced by hand: 11 wait states between a matrix instruction and a vector
+instruction touching its result (here: always a whole step apart, except in the blocks out of line, which wait);
+results of v_exp_f32 are consumed several instructions later; 3 wait states between a dot-product instruction and
+another kind of instruction reading its result, 2 between v_cvt_pk and the dot product reading it; 2 around
+v_permlane32_swap.
 """
 import os
 
