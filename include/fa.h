@@ -83,7 +83,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * With W = B*H*ceil(Nq/256), fa_fwd picks SPLIT when W < 256; for causal problems with
  * Nq > 768: WIDE_FOLD when Nq <= 4096, W <= 1024 and the last round of 256 workgroups is at
  * least 85% full, else SPLIT when W < 640 (Nq <= 4096) or W < 384 (longer); otherwise WIDE64 when
- * D = 128 and Nq >= 8192, else WIDE.
+ * D = 128 and a query sees 4096 keys or more on average (Nk, or Nk - Nq/2 when causal), else WIDE.
  * fa_set_option(FA_OPT_FWD_MODE, ...) overrides the choice (tests, tuning).
  * Nq = 1 (one decoding step) takes none of these: FA_MODE_STREAM, the register-streaming kernel
  * described at fa_fwd_splitkv, one workgroup per (batch, head) -- full speed when B*H fills the

@@ -149,7 +149,7 @@ bool use_streaming_decode(int Nq) { return Nq == 1 && option(FA_OPT_DECODE_KERNE
 //    FA_MODE_SPLIT, whose shorter chains matter more than its extra K/V traffic;
 //  * otherwise FA_MODE_WIDE: with many rounds the heavy-first dynamic dispatch evens out the triangle.
 // fa_set_option(FA_OPT_FWD_MODE, ...) overrides.
-int choose_mode(int B, int H, int Nq, int D, int causal) {
+int choose_mode(int B, int H, int Nq, int Nk, int D, int causal) {
     const int forced = option(FA_OPT_FWD_MODE);
     if (forced == FA_MODE_SPLIT || forced == FA_MODE_WIDE) return forced;
     if (forced == FA_MODE_WIDE64) return D == 128 ? FA_MODE_WIDE64 : FA_MODE_WIDE;
@@ -164,8 +164,10 @@ int choose_mode(int B, int H, int Nq, int D, int causal) {
         if (Nq <= 4096 ? W < 640 : W < 384) return FA_MODE_SPLIT;
     }
     // long walks at D = 128: the 64-row waves with the pipelined loop (the loop takes whole unmasked tiles two at
-    // a time, so it needs walks long enough to consist mostly of those)
-    if (D == 128 && Nq >= 8192) return FA_MODE_WIDE64;
+    // a time, so it needs walks long enough to consist mostly of those: measured faster from about 64 tiles per
+    // workgroup on average -- 1-2% -- and 2-14% slower at 32 tiles and below)
+    const long long avg_keys = causal ? (long long)Nk - Nq / 2 : (long long)Nk;
+    if (D == 128 && avg_keys >= 4096) return FA_MODE_WIDE64;
     return FA_MODE_WIDE;
 }
 
@@ -352,7 +354,7 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
         plan->lds_bytes = DECODE_WAVES * (512 / D) * (D + 2) * 4;     // one partial state per lane group
         return FA_OK;
     }
-    const int mode = choose_mode(B, H, Nq, D, causal);
+    const int mode = choose_mode(B, H, Nq, Nk, D, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
@@ -380,7 +382,7 @@ int fa_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return FA_ERR_ALIGN;
     if ((uintptr_t)lse & 3) return FA_ERR_ALIGN;
 
-    const int mode = use_streaming_decode(Nq) ? FA_MODE_STREAM : choose_mode(B, H, Nq, D, causal);
+    const int mode = use_streaming_decode(Nq) ? FA_MODE_STREAM : choose_mode(B, H, Nq, Nk, D, causal);
     const int BM = mode == FA_MODE_SPLIT ? 128 : 256;   // query rows per workgroup
     const long long nqt = ((long long)Nq + BM - 1) / BM;
     const long long nwork = (long long)B * H * nqt;
@@ -644,7 +646,9 @@ int check_attn_linear(const void *q, const void *k, const void *v, const void *w
 int block_attention(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int Nq, int Nk,
                     int D, float scale, int causal, int dtype, int row_first, int row_count, hipStream_t st) {
     {
-        const int mode = choose_mode(B, H, row_count, D, causal);
+        // (the keys the block's rows can see end at its last row's diagonal)
+        const int nk_seen = causal ? Nk - (Nq - row_first - row_count) : Nk;
+        const int mode = choose_mode(B, H, row_count, nk_seen > 0 ? nk_seen : 1, D, causal);
         const int BM = mode == FA_MODE_SPLIT ? 128 : 256;
         const long long nqt = ((long long)row_count + BM - 1) / BM;
         const long long nwork = (long long)B * H * nqt;

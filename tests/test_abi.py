@@ -269,6 +269,9 @@ def test_mode_heuristic_and_override(lib, monkeypatch):
     assert fa.fa_fwd_plan(1, 32, 131072, 131072, 128, 1, 1).mode == fa.FA_MODE_WIDE64
     assert fa.fa_fwd_plan(8, 32, 8192, 8192, 64, 1, 1).mode == fa.FA_MODE_WIDE         # D = 64: no such kernel
     assert fa.fa_fwd_plan(16, 32, 2048, 2048, 128, 1, 1).mode == fa.FA_MODE_WIDE       # short walks stay
+    assert fa.fa_fwd_plan(8, 32, 4096, 4096, 128, 1, 1).mode == fa.FA_MODE_WIDE        # 2048 keys on average
+    assert fa.fa_fwd_plan(4, 32, 4096, 4096, 128, 0, 1).mode == fa.FA_MODE_WIDE64      # not causal: all 4096
+    assert fa.fa_fwd_plan(8, 32, 512, 8192, 128, 1, 1).mode == fa.FA_MODE_WIDE64       # a chunk against a long cache
     assert fa.fa_fwd_plan(4, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE_FOLD  # four full rounds
     assert fa.fa_fwd_plan(5, 32, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_WIDE       # more: dynamic dispatch
     assert fa.fa_fwd_plan(1, 40, 2048, 2048, 128, 1, 0).mode == fa.FA_MODE_SPLIT      # 1.25 rounds: fold would idle
