@@ -235,7 +235,7 @@ def chunked_entry(I, torch, fa, steps, warmup):
             "kv_gb_per_s": round(kv_bytes / (ms * 1e-3) / 1e9, 1),
             "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(tf / MFMA_PEAK_TFLOPS, 4), **traffic_fields("splitkv_CHUNK"),
-                         "kernel": "fa_fwd_kernel (wide, split-KV) + fa_combine_kernel", "flops_per_call": fl,
+                         "kernel": "fa_fwd_wide64_kernel (split-KV) + fa_combine_kernel", "flops_per_call": fl,
                          "note": "K and V are read once (512 MiB): at this arithmetic intensity (about 500 flop per "
                                  "byte) the HBM roofline allows 4 PFLOP/s, so the matrix peak is the bound"}}
 

@@ -125,7 +125,9 @@ int fa_fwd_plan(int B, int H, int Nq, int Nk, int D, int causal, int dtype, fa_p
  * Bound by reading K and V once from HBM.  Nq = 1, the decoding step proper, runs a kernel of its
  * own that streams K and V through registers (one multiply-add per element leaves the matrix
  * cores nothing to reuse) and keeps the probabilities in fp32; fa_set_option(FA_OPT_DECODE_KERNEL, 1)
- * sends it through the tile kernel instead (tests, tuning).
+ * sends it through the tile kernel instead (tests, tuning).  With several query blocks per head (a chunk
+ * of a chunked prefill: Nq > 256) the call is bound by the matrix cores instead, and at D = 128 runs of 4096
+ * keys or more go to the kernel of FA_MODE_WIDE64.
  *
  *   nsplit          : > 0: number of runs (clamped to the number of 64-key tiles, at most 1024);
  *                     <= 0: the library picks (256 workgroups at D = 128 and for a single query,
@@ -339,7 +341,8 @@ int fa_mask_interior_run(const fa_mask_t *mask, int kv_len, int Nq, int Nk, int 
  * environment variable is read anywhere in the library.
  *
  *   FA_OPT_FWD_MODE      : FA_MODE_SPLIT, FA_MODE_WIDE, FA_MODE_WIDE_FOLD (causal problems only; WIDE
- *                          otherwise), FA_MODE_WIDE64 (D = 128 only; WIDE otherwise) or FA_AUTO
+ *                          otherwise), FA_MODE_WIDE64 (D = 128 only; WIDE otherwise) or FA_AUTO.
+ *                          FA_MODE_WIDE also keeps fa_fwd_splitkv's long runs on the tile kernel
  *   FA_OPT_DECODE_KERNEL : 0 or FA_AUTO: Nq = 1 runs the register-streaming kernel; 1: the tile kernels
  *   FA_OPT_LINEAR_TILE   : 128, 256 or FA_AUTO: token rows per workgroup tile of the projection
  *   FA_OPT_LINEAR_PANEL  : >= 1 or FA_AUTO: row tiles per panel of the projection's tile order

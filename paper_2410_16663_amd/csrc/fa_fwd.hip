@@ -81,8 +81,17 @@ hipError_t launch_masked(const FaParams &p, int nwork_padded, hipStream_t stream
 }
 
 template <int DT, int D, bool CAUSAL>
-hipError_t launch_splitkv(const FaParams &p, int nwork_padded, long long rows, hipStream_t stream) {
-    hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, true, true>), dim3(nwork_padded, p.nsplit), dim3(512), 0, stream, p);
+hipError_t launch_splitkv(const FaParams &p, int nwork_padded, long long rows, bool long_runs, hipStream_t stream) {
+    // long runs of a compute-bound shape (several query blocks per head) at D = 128: the 64-row waves with the
+    // pipelined loop; everything else the tile kernel's split-KV instantiation, which is tuned for streaming K/V
+    if constexpr (D == 128) {
+        if (long_runs)
+            hipLaunchKernelGGL((fa_fwd_wide64_kernel<DT, CAUSAL, true>), dim3(nwork_padded, p.nsplit), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, true, true>), dim3(nwork_padded, p.nsplit), dim3(512), 0, stream, p);
+    } else {
+        hipLaunchKernelGGL((fa_fwd_kernel<DT, D, CAUSAL, true, true>), dim3(nwork_padded, p.nsplit), dim3(512), 0, stream, p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr int RPB = 256 / (D / 4);            // rows per combine block
@@ -473,16 +482,20 @@ int fa_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *
         }
         return FA_OK;
     }
+    // keys a query sees per run, on average (as in choose_mode): from 4096 the wide64 kernel is the faster one
+    const long long avg_keys = causal ? (long long)Nk - Nq / 2 : (long long)Nk;
+    const bool long_runs = D == 128 && !p.kv_stream && option(FA_OPT_FWD_MODE) != FA_MODE_WIDE &&
+                           avg_keys / pl.nsplit >= 4096;
     const int key = (dtype << 2) | ((D == 128) << 1) | (causal ? 1 : 0);
     switch (key) {
-        case 0: e = launch_splitkv<0, 64, false>(p, pl.grid_x, rows, st); break;
-        case 1: e = launch_splitkv<0, 64, true>(p, pl.grid_x, rows, st); break;
-        case 2: e = launch_splitkv<0, 128, false>(p, pl.grid_x, rows, st); break;
-        case 3: e = launch_splitkv<0, 128, true>(p, pl.grid_x, rows, st); break;
-        case 4: e = launch_splitkv<1, 64, false>(p, pl.grid_x, rows, st); break;
-        case 5: e = launch_splitkv<1, 64, true>(p, pl.grid_x, rows, st); break;
-        case 6: e = launch_splitkv<1, 128, false>(p, pl.grid_x, rows, st); break;
-        case 7: e = launch_splitkv<1, 128, true>(p, pl.grid_x, rows, st); break;
+        case 0: e = launch_splitkv<0, 64, false>(p, pl.grid_x, rows, long_runs, st); break;
+        case 1: e = launch_splitkv<0, 64, true>(p, pl.grid_x, rows, long_runs, st); break;
+        case 2: e = launch_splitkv<0, 128, false>(p, pl.grid_x, rows, long_runs, st); break;
+        case 3: e = launch_splitkv<0, 128, true>(p, pl.grid_x, rows, long_runs, st); break;
+        case 4: e = launch_splitkv<1, 64, false>(p, pl.grid_x, rows, long_runs, st); break;
+        case 5: e = launch_splitkv<1, 64, true>(p, pl.grid_x, rows, long_runs, st); break;
+        case 6: e = launch_splitkv<1, 128, false>(p, pl.grid_x, rows, long_runs, st); break;
+        case 7: e = launch_splitkv<1, 128, true>(p, pl.grid_x, rows, long_runs, st); break;
         default: return FA_ERR_SHAPE;
     }
     if (e != hipSuccess) {

@@ -228,7 +228,7 @@ class Gen:
 
     def check_list(self):
         """Both row blocks' sums and the test sum <= 256 (which proves that no exponential exceeded 256), leaving the
-        verdict in vcc: the last vector instructions of a step."""
+        outcome in vcc: the last vector instructions of a step."""
         L = ["s_nop 3"]
         for rb in (0, 1):
             L.append(f"v_add_f32 {T(rb, 0)}, {T(rb, 0)}, {T(rb, 1)}")

@@ -309,8 +309,8 @@ def test_build_report_shows_register_only_kernels():
     build.build(force=True)
     # attention: 2 dtypes x 2 head dims x (causal x (split, wide, wide + split-KV) + descriptor mask);
     # paired fold: 2 dtypes x 2 head dims; combine: the same; output projection: 2 dtypes x 2 head dims x 2 tile
-    # heights; streaming decode: 2 dtypes x 2 head dims x (plain, masked); 64-row waves: 2 dtypes x causal
-    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 8 + 4
+    # heights; streaming decode: 2 dtypes x 2 head dims x (plain, masked); 64-row waves: 2 dtypes x causal x (plain, split-KV)
+    assert len(build.last_report) == 24 + 4 + 4 + 4 + 8 + 8 + 8
     for name, rep in build.last_report.items():
         assert rep["ScratchSize [bytes/lane]"] == 0 and rep["VGPRs Spill"] == 0, name
         assert rep["VGPRs"] + rep.get("AGPRs", 0) <= (512 if "fa_fwd_wide64_kernel" in name else 256), name

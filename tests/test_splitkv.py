@@ -71,6 +71,30 @@ def test_chunked_prefill_shapes_elementwise(oracle, shape, nsplit, causal, dtype
     check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"{shape} nsplit={nsplit} causal={causal} dt={dtype}")
 
 
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shape,nsplit", [((1, 2, 512, 20000, 128), 2), ((1, 2, 512, 20001, 128), 4),
+                                          ((1, 1, 700, 13000, 128), 3), ((2, 1, 300, 9000, 128), 2),
+                                          ((1, 1, 1100, 12345, 128), 2)])
+def test_long_runs_of_several_query_blocks(oracle, shape, nsplit, causal, dtype):
+    """Several query blocks per head against runs of 4096 keys and more at D = 128: fa_fwd_splitkv gives those runs
+    to the kernel with 64-row waves and the pipelined loop (every other split-KV shape to the tile kernel): runs that
+    start and end anywhere in the cache, ragged last tiles, ragged row blocks, runs wholly before or partly above
+    the diagonal; and the same call kept on the tile kernel gives the same result to the tolerance."""
+    B, H, Nq, Nk, D = shape
+    print(f"case splitkv long runs shape={shape} nsplit={nsplit} causal={causal} dtype={dtype}", flush=True)
+    rng = np.random.default_rng(hash((shape, nsplit, causal, dtype, 7)) % (2**32))
+    q, k, v = (rand_bits(rng, (B, H, n, D), dtype) for n in (Nq, Nk, Nk))
+    scale = 1.0 / math.sqrt(D)
+    o_ref, lse_ref = oracle.attention_fwd(q, k, v, scale, causal, dtype)
+    o, lse, plan = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
+    assert plan.nsplit == nsplit
+    check_against_oracle(o, lse, o_ref, lse_ref, dtype, f"long runs {shape} nsplit={nsplit} causal={causal} dt={dtype}")
+    options.set_fwd_mode("wide")          # keeps the tile kernel's split-KV instantiation
+    o2, lse2, _ = run_fa_fwd_splitkv(q, k, v, scale, causal, dtype, nsplit)
+    check_against_oracle(o2, lse2, o_ref, lse_ref, dtype, f"long runs, tile kernel {shape}")
+
+
 def test_rows_without_visible_keys(oracle):
     """Causal with Nq > Nk: the first rows see nothing in any run -> o = 0, lse = -inf."""
     print("case splitkv empty rows", flush=True)
